@@ -1,0 +1,179 @@
+/*
+ * otverify: target-side verification step of cross-vocabulary speculative decoding on one MI355X (gfx950).
+ *
+ * The operation is the verification half of OmniDraft's Algorithm 1 (Cross-vocabulary Speculative Decoding):
+ * given the target model's final hidden states for the k+1 verified positions of each sequence, the drafter's
+ * logits and drafted ids, a direct draft->target id map and an n-gram cache (Section "Cross-vocabulary N-gram
+ * Cache"), it
+ *   - projects the hidden states through the LM head and forms softmax statistics of the target rows and of
+ *     the draft rows (the "compute target probabilities on mapped tokens in parallel" step of Algorithm 1);
+ *   - translates the drafted ids into target-vocabulary tokens t_j with probabilities q'(t_j) (Eq. 1): direct
+ *     id lookup, or one target token for several consecutive draft tokens that hit the cache, whose
+ *     probability is the product of the sub-token probabilities;
+ *   - accepts t_j while u_j < min(1, p(t_j)/q'(t_j)) (Algorithm 1, rejection sampling step);
+ *   - draws the final token from norm(max(0, p - q')) at the first rejected position, with q' extended to the
+ *     whole target vocabulary by Eq. 2, or a free token from p when everything was accepted (Algorithm 1).
+ *
+ * Conventions
+ *   - Every function returns OT_OK (0) or a negative OT_ERR_*; nothing throws, aborts or prints.
+ *     ot_last_error() returns a thread-local, NUL-terminated description of the last failure on this thread.
+ *   - Pointers are marked HOST or DEVICE.  The library never frees or reallocates caller memory.
+ *   - Device work is enqueued on the stream given at init and is asynchronous: the caller synchronises
+ *     before reading outputs.  One context must not be used from two threads at once.
+ *   - Uniform random numbers are Philox4x32-10 (Salmon et al., SC'11) with key = (seed low, seed high) and
+ *     counter = (mapped position j, step, seq_id low, seq_id high).  Output word 0 gives the acceptance
+ *     uniform of position j, word 1 the uniform of the final-token draw at row j; a uniform is the word's top
+ *     24 bits times 2^-24.
+ */
+#ifndef OTVERIFY_H_
+#define OTVERIFY_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- status codes ------------------------------------------------------------------------------------- */
+#define OT_OK                 0
+#define OT_ERR_NULL          -1   /* a required pointer is NULL                                              */
+#define OT_ERR_SHAPE         -2   /* a size is out of range, over capacity, or row offsets are not monotone  */
+#define OT_ERR_DTYPE         -3   /* dtype is neither OT_BF16 nor OT_F32                                     */
+#define OT_ERR_MAP           -4   /* direct map entry out of range, or two draft ids share a target id       */
+#define OT_ERR_NGRAM         -5   /* n-gram entry length or id out of range                                  */
+#define OT_ERR_CTX_MISMATCH  -6   /* the n-gram cache was built for another context                          */
+#define OT_ERR_HIP           -7   /* a HIP call failed; ot_last_error() carries hipGetErrorString            */
+#define OT_ERR_NOMEM         -8   /* host or device allocation failed                                        */
+
+/* ---- storage types of hidden states, LM-head weights and draft logits --------------------------------- */
+#define OT_BF16 0
+#define OT_F32  1
+
+/* ---- per-sequence output flags ------------------------------------------------------------------------ */
+#define OT_FLAG_UNMAPPABLE 1      /* a drafted id had neither a cache hit nor a direct image: proposal cut   */
+#define OT_FLAG_RESID_ZERO 2      /* the residual had zero mass: final token drawn from p instead            */
+#define OT_FLAG_BAD_ID     4      /* a drafted id was outside [0, V_d): the sequence emits nothing           */
+
+#define OT_MAX_NGRAM_LEN   8      /* largest supported key length of a cache entry                           */
+#define OT_MAX_K          63      /* largest supported number of drafted tokens per sequence                 */
+
+typedef struct ot_ctx ot_ctx;                 /* owns the packed LM head, maps and workspace                  */
+typedef struct ot_ngram_cache ot_ngram_cache; /* owns the device hash table of one n-gram cache               */
+
+/* ---- ot_verify_init ----------------------------------------------------------------------------------- */
+typedef struct ot_verify_config {
+  int32_t d;               /* hidden size; for OT_BF16 a multiple of 8                                        */
+  int32_t V_t;             /* target vocabulary size                                                          */
+  int32_t V_d;             /* draft vocabulary size                                                           */
+  int32_t max_batch;       /* capacity: B <= max_batch                                                        */
+  int32_t max_k;           /* capacity: k_b <= max_k <= OT_MAX_K; rows <= max_batch * (max_k + 1)             */
+  int32_t dtype;           /* OT_BF16 or OT_F32: type of W, hidden and draft_logits                           */
+  int32_t max_ngram_len;   /* 2..OT_MAX_NGRAM_LEN: longest key any cache used with this context may hold      */
+  int32_t reserved;        /* must be 0                                                                       */
+  const void*    W;        /* DEVICE [d, V_t] row-major LM-head weights (z = h . W).  Read during init only:
+                              OT_BF16 weights are re-tiled into a private copy, OT_F32 weights are copied.    */
+  const int32_t* direct_map; /* HOST [V_d]: target id of each draft id, or -1.  Must be one-to-one on the
+                              mapped part (the paper's t_i <-> d_i), else OT_ERR_MAP.                         */
+  void*          stream;   /* hipStream_t on which all device work of this context is enqueued (NULL = the
+                              default stream)                                                                 */
+} ot_verify_config;
+
+/* Creates a context on the current HIP device.  Allocates the private LM-head copy (d * V_t elements), the
+ * two map tables and a workspace sized for max_batch * (max_k + 1) rows of fp32 logits.  Synchronises the
+ * stream before returning.  *out is NULL on failure.                                                         */
+int  ot_verify_init(const ot_verify_config* cfg, ot_ctx** out);
+void ot_verify_destroy(ot_ctx* ctx);          /* synchronises the stream, frees everything; NULL is a no-op   */
+
+/* ---- ot_ngram_cache_build ------------------------------------------------------------------------------ */
+/* The n-gram cache C = {(t_i, [d_j]_{j=1:n})} (Section "Cross-vocabulary N-gram Cache") in CSR form on the
+ * HOST: entry e maps draft ids key_ids[key_off[e] .. key_off[e+1]) (2 <= length <= cfg.max_ngram_len, ids in
+ * [0, V_d)) to target_ids[e] in [0, V_t).  Of entries with equal keys the last one wins.  n_entries may be 0.
+ * Builds an open-addressing hash table on the host and copies it to the device (synchronous).  The arrays
+ * are not referenced after return.  The cache may be used only with the context it was built for and must
+ * be destroyed before that context.                                                                          */
+int  ot_ngram_cache_build(ot_ctx* ctx, int32_t n_entries, const int32_t* key_off, const int32_t* key_ids,
+                          const int32_t* target_ids, ot_ngram_cache** out);
+void ot_ngram_cache_destroy(ot_ngram_cache* cache);
+
+/* ---- ot_verify_step ------------------------------------------------------------------------------------ */
+/* Ragged batch: sequence b drafted k_b tokens and owns the k_b + 1 rows row_off[b] .. row_off[b+1]-1; row j of
+ * a sequence is the target's hidden state that predicts mapped token t_j (Algorithm 1: p(t_t) .. p(t_{t+m})).
+ * M = row_off[B] rows in total, K = M - B drafted positions; the k_b draft rows of sequence b start at draft
+ * row row_off[b] - b.                                                                                         */
+typedef struct ot_step_in {
+  int32_t         B;                  /* number of sequences, 0 <= B <= max_batch                             */
+  uint32_t        step;               /* Philox counter word 1                                                */
+  const int32_t*  row_off;            /* DEVICE [B+1]                                                         */
+  const int32_t*  row_off_host;       /* HOST   [B+1], same values; used for validation and launch sizes      */
+  const void*     hidden;             /* DEVICE [M, d] row-major, cfg.dtype                                   */
+  const void*     draft_logits;       /* DEVICE [K, V_d] row-major, cfg.dtype                                 */
+  const int32_t*  draft_ids;          /* DEVICE [K] drafted ids d_i                                           */
+  const float*    temperature;        /* DEVICE [B]; 0 selects the greedy rule for that sequence              */
+  const float*    draft_temperature;  /* DEVICE [B], or NULL: the drafter used `temperature`                  */
+  const uint64_t* seq_id;             /* DEVICE [B] Philox stream id of each sequence                         */
+  uint64_t        seed;               /* Philox key                                                           */
+} ot_step_in;
+
+/* Caller-allocated DEVICE buffers, all required.  Per sequence ([B]):
+ *   n_mapped        m_b, number of target-vocabulary tokens the proposal translated into
+ *   n_accept        n_b <= m_b, accepted mapped tokens (the correction / free token is not counted)
+ *   n_accept_draft  the same in draft-token units, sum of the accepted spans' lengths
+ *   n_emit          tokens written to out_tokens: n_b + 1, or 0 with OT_FLAG_BAD_ID
+ *   hits_proposed   mapped tokens that came from the n-gram cache; hits_accepted: those among the accepted
+ *   flags           OR of OT_FLAG_*
+ * Per row ([M], entry row_off[b] + j belongs to mapped position j of sequence b):
+ *   out_tokens      j < n_b: accepted t_j; j == n_b: the correction or free token; other entries -1
+ *   mapped_ids      t_j for j < m_b, else -1;  span_start / span_len: the draft positions t_j covers (else -1/0)
+ *   p_tok, q_tok, ratio  p_j(t_j), q'(t_j), min(1, p/q') for j < m_b, else 0.  For a greedy sequence p_tok is
+ *                   1 or 0 (argmax match) and ratio equals it.                                                */
+typedef struct ot_step_out {
+  int32_t *n_mapped, *n_accept, *n_accept_draft, *n_emit, *hits_proposed, *hits_accepted, *flags;
+  int32_t *out_tokens, *mapped_ids, *span_start, *span_len;
+  float   *p_tok, *q_tok, *ratio;
+} ot_step_out;
+
+/* Enqueues one verification step.  `cache` may be NULL (direct map only).  Returns OT_ERR_SHAPE if B or any
+ * k_b exceeds the capacity or row_off_host is not increasing by at least 1 per sequence.  B == 0 is a no-op. */
+int ot_verify_step(ot_ctx* ctx, const ot_ngram_cache* cache, const ot_step_in* in, ot_step_out* out);
+
+/* Same, but the LM-head projection is skipped and `target_logits` (DEVICE [M, V_t] row-major fp32, the z_j of
+ * Algorithm 1's target pass) is used instead; in->hidden is ignored.                                          */
+int ot_verify_step_from_logits(ot_ctx* ctx, const ot_ngram_cache* cache, const ot_step_in* in,
+                               const float* target_logits, ot_step_out* out);
+
+/* ---- diagnostics ---------------------------------------------------------------------------------------- */
+/* Device pointers into the context's workspace, valid until ot_verify_destroy and overwritten by every step.
+ * Row statistics are those of the softmax of the Notation paragraph: p_j(v) = exp((z_v - row_max)/T) / row_sumexp. */
+typedef struct ot_workspace_view {
+  const float*   logits;        /* [rows, ld_logits] fp32 target logits of the last ot_verify_step            */
+  int64_t        ld_logits;
+  const float*   row_max;       /* [M]                                                                        */
+  const double*  row_sumexp;    /* [M] sum_v exp((z_v - row_max)/T_b); T_b == 0 rows use T = 1                */
+  const int32_t* row_argmax;    /* [M] lowest index of the maximum                                            */
+  const float*   draft_row_max; /* [K] the same three statistics of the draft rows at the draft temperature   */
+  const double*  draft_row_sumexp;
+  const int32_t* draft_row_argmax;
+} ot_workspace_view;
+int ot_verify_workspace(ot_ctx* ctx, ot_workspace_view* view);
+
+/* Kernel timing.  While enabled, every step records HIP events between its kernels on the context's stream.
+ * ot_verify_profile_read synchronises the stream, adds the elapsed milliseconds of the steps run since the
+ * last read into ms[0 .. OT_N_STAGES) (overwriting it), stores the number of steps in *n_steps and resets.    */
+#define OT_STAGE_DRAFT_STATS   0   /* softmax statistics of the draft rows                                    */
+#define OT_STAGE_MAP           1   /* translation scan and n-gram cache probes (Eq. 1)                        */
+#define OT_STAGE_LM_HEAD       2   /* z = h . W                                                               */
+#define OT_STAGE_TARGET_STATS  3   /* softmax statistics of the target rows                                   */
+#define OT_STAGE_ACCEPT        4   /* acceptance ratios, Philox uniforms, first rejection                     */
+#define OT_STAGE_RESID_SUMS    5   /* partial masses of max(0, p - q') (Eq. 2) at the final row               */
+#define OT_STAGE_RESID_PICK    6   /* inverse-CDF pick of the final token                                     */
+#define OT_N_STAGES            7
+int ot_verify_profile(ot_ctx* ctx, int32_t enable);
+int ot_verify_profile_read(ot_ctx* ctx, float* ms, int32_t* n_steps);
+
+const char* ot_last_error(void);
+const char* ot_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OTVERIFY_H_ */

@@ -172,7 +172,12 @@ def residual(p: np.ndarray, qp: np.ndarray) -> np.ndarray:
 
 
 def sample_inverse_cdf(r: np.ndarray, u: float):
-    """Token = min{v : c_v > u * c_last}, c = running sum of r in ascending id.  Returns (v, margin)."""
+    """Token = min{v : c_v > u * c_last}, c = running sum of r in ascending id.
+
+    Returns (v, margin, (prev, next)): margin is the distance of u * c_last to the nearer edge of v's cell as a
+    fraction of the total mass; prev / next are the nearest ids below / above v with r > 0 (-1 if none).  The
+    last two are diagnostics for comparisons against lower-precision implementations.
+    """
     c = np.cumsum(r)
     total = c[-1]
     x = u * total
@@ -181,7 +186,11 @@ def sample_inverse_cdf(r: np.ndarray, u: float):
         v = int(np.flatnonzero(r > 0)[-1])
     below = c[v - 1] if v > 0 else 0.0
     margin = min(x - below, c[v] - x) / total
-    return v, float(margin)
+    support = np.flatnonzero(r > 0)
+    at = int(np.searchsorted(support, v))
+    prev_id = int(support[at - 1]) if at > 0 else -1
+    next_id = int(support[at + 1]) if at + 1 < support.size else -1
+    return v, float(margin), (prev_id, next_id)
 
 
 def verify_step(*, row_off, draft_ids, draft_logits, direct_map, V_t: int, cache: Optional[dict],
@@ -213,6 +222,7 @@ def verify_step(*, row_off, draft_ids, draft_logits, direct_map, V_t: int, cache
         "u_margin": np.full(M, np.inf), "cdf_margin": np.full(B, np.inf), "top2_gap": np.full(M, np.inf),
         "row_max": Z.max(axis=1) if M else np.zeros(0), "row_argmax": Z.argmax(axis=1) if M else np.zeros(0, np.int64),
         "row_sumexp": np.zeros(M), "final_row": np.full(B, -1, np.int32),
+        "cdf_neighbors": np.full((B, 2), -1, np.int64),
     }
     if return_logits:
         out["logits"] = Z
@@ -292,9 +302,10 @@ def verify_step(*, row_off, draft_ids, draft_logits, direct_map, V_t: int, cache
                 out["flags"][b] |= FLAG_RESID_ZERO
                 r = p_n
         _, u2 = uniforms(seed, seq_id[b], step, n)
-        v, margin = sample_inverse_cdf(r, u2)
+        v, margin, neighbors = sample_inverse_cdf(r, u2)
         out["out_tokens"][r0 + n] = v
         out["cdf_margin"][b] = margin
+        out["cdf_neighbors"][b] = neighbors
     return out
 
 

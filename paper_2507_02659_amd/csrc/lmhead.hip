@@ -1,0 +1,187 @@
+// LM-head projection z = h . W for the k+1 verified rows of every sequence (Algorithm 1, the target pass that
+// yields p(t_t) .. p(t_{t+m}) in parallel): Z[M, V_t] (fp32) = H[M, d] (bf16) x W[d, V_t] (bf16), fp32 accumulate.
+//
+// At verification time M = sum_b (k_b + 1) is a few rows to a few hundred, so the product is bound by streaming
+// the d x V_t weights from HBM exactly once, not by the matrix cores.  The design follows from that:
+//   * W is re-tiled once at init into the register layout of v_mfma_f32_16x16x32_bf16 operands: the fragment for
+//     16 vocabulary columns x 32 hidden indices is 64 lanes x 16 bytes, stored contiguously, and the four
+//     fragments one wavefront needs per 32-deep step are adjacent.  A wavefront therefore streams its 64 columns
+//     with fully coalesced 16-byte loads straight into MFMA operand registers: no LDS round trip, no transpose.
+//   * Every weight is used by exactly one wavefront, which keeps accumulators for ALL rows of the M-block
+//     (up to 9 x 16 rows x 64 columns = 144 registers), so W never has to be re-read for another row tile.
+//   * The hidden rows, shared by the four wavefronts of a workgroup, are staged through LDS in 128-deep slices
+//     (padded rows: conflict-free 16-byte reads); each hidden fragment read from LDS feeds four MFMAs.
+//   * Weight fragments are prefetched kPrefetch steps ahead in registers to keep enough bytes in flight.
+// Operand roles: the weight fragment is MFMA operand A and the hidden fragment operand B, so a lane ends up with
+// four consecutive vocabulary columns of one row and stores them as one float4.
+#include "otv_internal.h"
+
+namespace otv {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kKC = kGemmKPad;        // hidden slice staged in LDS per barrier pair
+constexpr int kKSteps = kKC / 32;     // MFMA steps per slice
+constexpr int kLdsRow = kKC + 8;      // bf16 elements per padded LDS row (272 bytes)
+constexpr int kWavesPerWG = 4;
+
+// Packed layout (16-byte units): unit(((wt * nks + ks) * 4 + sub) * 64 + lane) holds
+//   W[ks*32 + 8*(lane/16) + e][wt*64 + sub*16 + lane%16], e = 0..7; zero outside [d, V_t].
+__global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict__ W, int d, int V_t,
+                                                     uint4* __restrict__ Wp, int nks, int64_t n_units) {
+  const int64_t u = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (u >= n_units) return;
+  const int lane = (int)(u & 63);
+  const int sub = (int)((u >> 6) & 3);
+  const int64_t rest = u >> 8;
+  const int ks = (int)(rest % nks);
+  const int wt = (int)(rest / nks);
+  const int n = wt * 64 + sub * 16 + (lane & 15);
+  const int kb = ks * 32 + 8 * (lane >> 4);
+  uint32_t w[4] = {0, 0, 0, 0};
+  if (n < V_t) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int kk = kb + e;
+      const uint32_t x = kk < d ? (uint32_t)W[(int64_t)kk * V_t + n] : 0u;
+      w[e >> 1] |= x << (16 * (e & 1));
+    }
+  }
+  Wp[u] = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+template <int MT, int PF>
+__global__ __launch_bounds__(256) void lmhead_bf16_kernel(const uint16_t* __restrict__ H, int M, int d,
+                                                          const uint4* __restrict__ Wp, int nks, int n_wtiles,
+                                                          float* __restrict__ Z, int V_t, int64_t ldz, int vec_store) {
+  static_assert(kKSteps % PF == 0, "prefetch depth must divide the steps per slice");
+  __shared__ __attribute__((aligned(16))) uint16_t sH[MT * 16 * kLdsRow];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int wt = blockIdx.x * kWavesPerWG + wave;
+  const bool active = wt < n_wtiles;
+  const int row0 = blockIdx.y * (MT * 16);
+  const uint4* wp = Wp + ((int64_t)(active ? wt : 0) * nks) * 256 + lane;
+
+  f32x4 acc[MT][4];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nw = 0; nw < 4; ++nw) acc[mt][nw] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  uint4 bq[PF][4];
+#pragma unroll
+  for (int s = 0; s < PF; ++s)
+#pragma unroll
+    for (int nw = 0; nw < 4; ++nw) bq[s][nw] = (active && s < nks) ? wp[(s * 4 + nw) * 64] : make_uint4(0, 0, 0, 0);
+
+  const int a_row = lane & 15, a_col = 8 * (lane >> 4);
+  for (int kc = 0; kc < nks; kc += kKSteps) {
+    __syncthreads();                       // the previous slice has been consumed
+    for (int idx = tid; idx < MT * 16 * (kKC / 8); idx += 256) {
+      const int r = idx / (kKC / 8), c = idx % (kKC / 8);
+      const int gr = row0 + r, gk = kc * 32 + c * 8;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (gr < M && gk < d) v = *reinterpret_cast<const uint4*>(H + (int64_t)gr * d + gk);
+      *reinterpret_cast<uint4*>(&sH[r * kLdsRow + c * 8]) = v;
+    }
+    __syncthreads();
+    if (active) {
+#pragma unroll
+      for (int ks = 0; ks < kKSteps; ++ks) {
+        const int kk = kc + ks;
+        uint4 bw[4];
+#pragma unroll
+        for (int nw = 0; nw < 4; ++nw) bw[nw] = bq[ks % PF][nw];
+        if (kk + PF < nks) {
+#pragma unroll
+          for (int nw = 0; nw < 4; ++nw) bq[ks % PF][nw] = wp[((int64_t)(kk + PF) * 4 + nw) * 64];
+        }
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const uint4 hv = *reinterpret_cast<const uint4*>(&sH[(mt * 16 + a_row) * kLdsRow + ks * 32 + a_col]);
+          const bf16x8 hf = __builtin_bit_cast(bf16x8, hv);
+#pragma unroll
+          for (int nw = 0; nw < 4; ++nw) {
+            acc[mt][nw] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bw[nw]), hf,
+                                                                  acc[mt][nw], 0, 0, 0);
+          }
+        }
+      }
+    }
+  }
+  if (!active) return;
+  // lane holds Z[row0 + mt*16 + lane%16][wt*64 + nw*16 + 4*(lane/16) + 0..3]
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    const int m = row0 + mt * 16 + (lane & 15);
+    if (m >= M) continue;
+#pragma unroll
+    for (int nw = 0; nw < 4; ++nw) {
+      const int n = wt * 64 + nw * 16 + 4 * (lane >> 4);
+      float* dst = Z + (int64_t)m * ldz + n;
+      if (vec_store && n + 3 < V_t) {
+        *reinterpret_cast<float4*>(dst) = make_float4(acc[mt][nw][0], acc[mt][nw][1], acc[mt][nw][2], acc[mt][nw][3]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (n + e < V_t) dst[e] = acc[mt][nw][e];
+      }
+    }
+  }
+}
+
+// fp32 path (small fp32 problems only): one thread per logit, coalesced over the vocabulary.
+__global__ __launch_bounds__(256) void lmhead_f32_kernel(const float* __restrict__ H, int M, int d,
+                                                         const float* __restrict__ W, float* __restrict__ Z, int V_t,
+                                                         int64_t ldz) {
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  const int m = blockIdx.y;
+  if (n >= V_t) return;
+  const float* h = H + (int64_t)m * d;
+  float acc = 0.f;
+  for (int kk = 0; kk < d; ++kk) acc = fmaf(h[kk], W[(int64_t)kk * V_t + n], acc);
+  Z[(int64_t)m * ldz + n] = acc;
+}
+
+template <int MT, int PF>
+hipError_t launch_one(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
+                      int64_t ldz, hipStream_t stream) {
+  const int nks = Kp / 32, n_wtiles = Vp / kGemmColsPerWave;
+  dim3 grid(ceil_div(n_wtiles, kWavesPerWG), ceil_div(M, MT * 16)), block(256);
+  const int vec_store = (ldz % 4 == 0) && (reinterpret_cast<uintptr_t>(Z) % 16 == 0);
+  hipLaunchKernelGGL((lmhead_bf16_kernel<MT, PF>), grid, block, 0, stream, H, M, d,
+                     reinterpret_cast<const uint4*>(Wp), nks, n_wtiles, Z, V_t, ldz, vec_store);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_pack_w_bf16(const uint16_t* W, int d, int V_t, uint16_t* Wp, int Kp, int Vp, hipStream_t stream) {
+  const int nks = Kp / 32;
+  const int64_t n_units = (int64_t)(Vp / 64) * nks * 256;
+  hipLaunchKernelGGL(pack_w_kernel, dim3((unsigned)((n_units + 255) / 256)), dim3(256), 0, stream, W, d, V_t,
+                     reinterpret_cast<uint4*>(Wp), nks, n_units);
+  return hipGetLastError();
+}
+
+hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
+                              int64_t ldz, hipStream_t stream) {
+  if (M == 0) return hipSuccess;
+  const int tiles = ceil_div(M, 16);
+  if (tiles <= 1) return launch_one<1, 4>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, stream);
+  if (tiles <= 3) return launch_one<3, 4>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, stream);
+  if (tiles <= 5) return launch_one<5, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, stream);
+  if (tiles <= 7) return launch_one<7, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, stream);
+  return launch_one<9, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, stream);
+}
+
+hipError_t launch_lmhead_f32(const float* H, int M, int d, const float* W, float* Z, int V_t, int64_t ldz,
+                             hipStream_t stream) {
+  if (M == 0) return hipSuccess;
+  hipLaunchKernelGGL(lmhead_f32_kernel, dim3(ceil_div(V_t, 256), M), dim3(256), 0, stream, H, M, d, W, Z, V_t, ldz);
+  return hipGetLastError();
+}
+
+}  // namespace otv

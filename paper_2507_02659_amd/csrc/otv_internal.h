@@ -1,0 +1,102 @@
+// Internal declarations shared by the host API and the kernel translation units of libotverify.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "otverify.h"
+
+namespace otv {
+
+// ------------------------------------------------------------------------------------------------ geometry
+constexpr int kStatThreads = 256;
+constexpr int kStatChunk = 4096;     // logits per workgroup of the softmax-statistics kernel
+constexpr int kResidTile = 4096;     // vocabulary entries per workgroup of the residual kernels
+constexpr int kGemmColsPerWave = 64; // LM-head columns owned by one wavefront
+constexpr int kGemmKPad = 128;       // packed K extent is a multiple of this
+
+inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+// ------------------------------------------------------------------------------------------------ n-gram table
+// Open addressing, linear probing.  Slot = { len, target, ids[max_len] } as int32; len == 0 marks an empty slot.
+struct CacheTable {
+  const int32_t* slots;
+  uint32_t mask;      // capacity - 1, capacity a power of two >= 2 * entries
+  int32_t stride;     // int32 words per slot = 2 + max_len
+  int32_t max_len;
+};
+
+__host__ __device__ inline uint32_t hash_ngram(const int32_t* ids, int len) {
+  uint32_t h = 0x9E3779B9u ^ (uint32_t)len;
+  for (int i = 0; i < len; ++i) {
+    h ^= (uint32_t)ids[i] + 0x7F4A7C15u + (h << 6) + (h >> 2);
+    h *= 0x85EBCA6Bu;
+    h ^= h >> 13;
+  }
+  h *= 0xC2B2AE35u;
+  h ^= h >> 16;
+  return h;
+}
+
+// ------------------------------------------------------------------------------------------------ per-step view
+// What the final-token kernels need to know about sequence b; written by the acceptance kernel.
+struct FinalInfo {
+  int32_t mode;     // 0: nothing to draw (greedy, or bad id), 2: draw from p (free token), 3: draw from the residual
+  int32_t row;      // global row of the final token (row_off[b] + n_b)
+  int32_t drow;     // global draft row whose distribution fills Eq. 2's "otherwise" branch
+  int32_t t_ng;     // target id of the n-gram matched at the rejected position, or -1
+  int32_t t_pre;    // direct image of that n-gram's first sub-token, or -1
+  int32_t pad;
+  double pi;        // product of the n-gram's sub-token probabilities
+  double q_pre;     // q(d_1) - pi
+  double u2;        // uniform of the draw
+};
+
+struct StepArgs {
+  // problem
+  int32_t B, M, K, d, V_t, V_d, dtype, max_ngram_len;
+  uint32_t step;
+  uint64_t seed;
+  // inputs (device)
+  const int32_t* row_off;
+  const void* hidden;
+  const void* draft_logits;
+  const int32_t* draft_ids;
+  const float* temperature;
+  const float* draft_temperature;
+  const uint64_t* seq_id;
+  const int32_t* dmap;   // [V_d]
+  const int32_t* tmap;   // [V_t]
+  CacheTable cache;      // slots == nullptr: no cache
+  // workspace (device)
+  const float* Z;        // [M, ldz]
+  int64_t ldz;
+  int32_t ncht, nchd;    // statistic chunks per target / draft row
+  float* tpart_max; double* tpart_sum; int32_t* tpart_arg;   // [M, ncht]
+  float* dpart_max; double* dpart_sum; int32_t* dpart_arg;   // [K, nchd]
+  float* row_max; double* row_sum; int32_t* row_arg;         // [M]
+  float* drow_max; double* drow_sum; int32_t* drow_arg;      // [K]
+  double* logq_tok;      // [K] log q_i(d_i)
+  double* logq_map;      // [M] log q'(t_j)
+  int32_t* s_end;        // [B] draft position where the scan stopped
+  FinalInfo* fin;        // [B]
+  int32_t ntiles;        // residual tiles per row
+  double* tile_r; double* tile_p;                            // [B, ntiles]
+  // outputs (device)
+  ot_step_out out;
+};
+
+// ------------------------------------------------------------------------------------------------ launchers
+// Each returns the hipError_t of its launch.  All work goes to `stream`.
+hipError_t launch_pack_w_bf16(const uint16_t* W, int d, int V_t, uint16_t* Wp, int Kp, int Vp, hipStream_t stream);
+hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
+                              int64_t ldz, hipStream_t stream);
+hipError_t launch_lmhead_f32(const float* H, int M, int d, const float* W, float* Z, int V_t, int64_t ldz,
+                             hipStream_t stream);
+hipError_t launch_stats(const StepArgs& a, bool draft, hipStream_t stream);
+hipError_t launch_map(const StepArgs& a, hipStream_t stream);
+hipError_t launch_accept(const StepArgs& a, hipStream_t stream);
+hipError_t launch_resid_sums(const StepArgs& a, hipStream_t stream);
+hipError_t launch_resid_pick(const StepArgs& a, hipStream_t stream);
+
+}  // namespace otv

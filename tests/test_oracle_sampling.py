@@ -216,8 +216,8 @@ def test_inverse_cdf_picks_the_right_cell_and_skips_zero_mass():
     r = np.array([0.0, 0.2, 0.0, 0.0, 0.5, 0.3, 0.0])
     for u, want in [(0.0, 1), (0.1999, 1), (0.2, 4), (0.6999, 4), (0.7, 5), (0.999999, 5)]:
         assert ov.sample_inverse_cdf(r, u)[0] == want
-    v, margin = ov.sample_inverse_cdf(r, 0.45)
-    assert v == 4 and margin == pytest.approx(0.25)
+    v, margin, nb = ov.sample_inverse_cdf(r, 0.45)
+    assert v == 4 and margin == pytest.approx(0.25) and nb == (1, 5)
 
 
 def test_temperature_zero_is_argmax_match():
