@@ -356,7 +356,7 @@ def baseline_spec(i: int, *, greedy: bool = False, scale: Optional[dict] = None)
     elif i == 3:
         s = CaseSpec(name="cfg3_qwen2_7b", dtype="bf16", d=3584, V_t=152064, V_d=32000, k=[5],
                      temperature=[1.0], n_direct=28000, n_ngram=20000, ngram_len=(2, 4), zipf_a=1.1,
-                     plant_cover=0.30, data_seed=1002, philox_seed=2)
+                     plant_cover=0.30, data_seed=10002, philox_seed=2)
     elif i == 4:
         s = CaseSpec(name="cfg4_llama3_8b_b16", dtype="bf16", d=4096, V_t=128256, V_d=32000, k=[8] * 16,
                      temperature=[0.7] * 16, n_direct=30000, n_ngram=50000, ngram_len=(2, 5), zipf_a=1.1,
