@@ -1,0 +1,166 @@
+"""Throughput of the verification step on one MI355X, with roofline figures and the CPU oracle timed beside it.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu]
+
+A "step" is one ot_verify_step over one synthetic batch: draft softmax statistics, translation (direct map +
+n-gram cache), LM-head projection, target softmax statistics, acceptance, residual mass and final-token draw.
+The workload is the configuration the headline metric is quoted on: Llama3-8B-shaped target, V_t = 128256,
+B = 16 sequences x k = 8 drafted tokens, bf16 (configuration 4).  Inputs are resident in HBM before the timed
+region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+
+
+def lm_head_bytes(M, d, V_t):
+    """Algorithmic HBM bytes of one LM-head launch: W read once, H read once, fp32 logits written once."""
+    return 2 * d * V_t + 2 * M * d + 4 * M * V_t
+
+
+def read_traffic_note(path):
+    """HBM bytes per LM-head launch measured offline with rocprofv3 --pmc, if a summary has been committed."""
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("hbm_bytes_per_launch:"):
+                    return float(line.split(":")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=4, help="BASELINE configuration 1..5 (default: the headline one)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build is single-GPU (no sharding, no collectives); run with --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2507_02659_amd import binding as ot
+    from paper_2507_02659_amd.runner import Verifier
+    from workloads import baseline_spec, make_case
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the verification path has no CPU fallback")
+
+    t0 = time.time()
+    case = make_case(baseline_spec(args.config))
+    sys.stderr.write(f"[bench] generated {case.name} in {time.time() - t0:.1f}s: B={case.B} M={case.M} K={case.K} "
+                     f"d={case.d} V_t={case.V_t} V_d={case.V_d}\n")
+    v = Verifier.for_case(case)
+    inp = v.upload(case)
+    from_logits = case.hidden is None
+
+    for i in range(args.warmup):
+        v.step(inp, from_logits=from_logits, step=i)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        v.step(inp, from_logits=from_logits, step=args.warmup + i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = case.K * args.steps / elapsed
+
+    # per-kernel durations: HIP events recorded by the library on its own stream between the step's kernels
+    ot.ot_verify_profile(v.ctx, True)
+    n_prof = min(args.steps, 1000)
+    for i in range(n_prof):
+        v.step(inp, from_logits=from_logits, step=args.warmup + i)
+    stage_ms, n_read = ot.ot_verify_profile_read(v.ctx)
+    ot.ot_verify_profile(v.ctx, False)
+    stage_us = {k: 1e3 * t / max(n_read, 1) for k, t in stage_ms.items()}
+
+    # one more step with the benchmark's own step index, kept for the parity note below
+    v.step(inp, from_logits=from_logits, step=case.step)
+    gpu = v.results(inp)
+
+    M, K, d, V_t, V_d = case.M, case.K, case.d, case.V_t, case.V_d
+    esz = 2 if case.dtype == "bf16" else 4
+    gemm_bytes = lm_head_bytes(M, d, V_t) if esz == 2 else 4 * d * V_t + 4 * M * d + 4 * M * V_t
+    gemm_s = stage_us["lm_head"] * 1e-6
+    achieved = gemm_bytes / gemm_s / 1e9 if gemm_s > 0 else 0.0
+    stats_bytes = 4 * M * V_t
+    extra = {
+        "stage_us": {k: round(x, 2) for k, x in stage_us.items()},
+        "lm_head_tflops": round(2.0 * M * d * V_t / gemm_s / 1e12, 1) if gemm_s > 0 else None,
+        "lm_head_frac_mfma_peak": round(2.0 * M * d * V_t / gemm_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4) if gemm_s > 0 else None,
+        "target_stats_gbs": round(stats_bytes / (stage_us["target_stats"] * 1e-6) / 1e9, 1) if stage_us["target_stats"] > 0 else None,
+        "target_stats_frac_hbm_peak": round(stats_bytes / (stage_us["target_stats"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if stage_us["target_stats"] > 0 else None,
+        "rows_per_s": round(M * args.steps / elapsed, 1),
+        "step_hbm_bytes": gemm_bytes + stats_bytes + esz * K * V_d + case.B * (4 * V_t + esz * V_d + 4 * V_t),
+    }
+    extra["step_frac_hbm_roofline"] = round(extra["step_hbm_bytes"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+
+    result = {
+        "metric": "verified draft positions/sec at V_t=128k",
+        "value": round(value, 1),
+        "unit": "positions/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": case.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"BASELINE configuration {args.config}: {case.name}", "B": case.B, "k": int(case.k.max()),
+                   "rows_M": M, "draft_positions_K": K, "d": d, "V_t": V_t, "V_d": V_d,
+                   "ngram_entries": int(case.ngram_target_ids.size)},
+        "roofline": {
+            "kernel": "lmhead_bf16_kernel" if esz == 2 else "lmhead_f32_kernel",
+            "bound": "hbm",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "algorithmic_bytes_per_launch": gemm_bytes,
+            "avg_launch_us": round(stage_us["lm_head"], 2),
+            "traffic": read_traffic_note(os.path.join(ROOT, "profiles", f"lm_head_cfg{args.config}_hbm_traffic.txt")),
+        },
+        "extra": extra,
+    }
+
+    if not args.no_cpu:
+        from oracle import verify as ov
+        import parity
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        t1 = time.perf_counter()
+        ref = ov.verify_case(case)
+        cpu_s = time.perf_counter() - t1
+        result["cpu_baseline"] = {
+            "value": round(case.K / cpu_s, 2), "unit": "positions/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"one whole step of the same workload ({case.B} sequences, {case.K} drafted positions), "
+                      f"NumPy float64, {cpu_s:.1f}s",
+        }
+        rep = parity.compare(case, gpu, ref, logits_from_gpu=not from_logits)
+        result["parity"] = {"summary": rep.summary(), "failures": len(rep.failures)}
+    v.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -22,10 +22,6 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kKC = kGemmKPad;        // hidden slice staged in LDS per barrier pair
-constexpr int kKSteps = kKC / 32;     // MFMA steps per slice
-constexpr int kLdsRow = kKC + 8;      // bf16 elements per padded LDS row (272 bytes)
-constexpr int kWavesPerWG = 4;
 
 // Packed layout (16-byte units): unit(((wt * nks + ks) * 4 + sub) * 64 + lane) holds
 //   W[ks*32 + 8*(lane/16) + e][wt*64 + sub*16 + lane%16], e = 0..7; zero outside [d, V_t].
@@ -52,14 +48,25 @@ __global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict_
   Wp[u] = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
-template <int MT, int PF>
-__global__ __launch_bounds__(256) void lmhead_bf16_kernel(const uint16_t* __restrict__ H, int M, int d,
-                                                          const uint4* __restrict__ Wp, int nks, int n_wtiles,
-                                                          float* __restrict__ Z, int V_t, int64_t ldz, int vec_store) {
-  static_assert(kKSteps % PF == 0, "prefetch depth must divide the steps per slice");
-  __shared__ __attribute__((aligned(16))) uint16_t sH[MT * 16 * kLdsRow];
+// ---------------------------------------------------------------------------------------------------------------
+// Wide kernel: M-blocks of up to MT*16 rows.  WPG wavefronts per workgroup, each owning 64 columns over the whole
+// hidden dimension; the hidden slice is double-buffered in LDS (next slice fetched into registers while the current
+// one feeds the MFMAs, written to the other buffer afterwards: one barrier per slice).
+template <int MT, int PF, int WPG, int KC>
+__global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16_t* __restrict__ H, int M, int d,
+                                                                    const uint4* __restrict__ Wp, int nks,
+                                                                    int n_wtiles, float* __restrict__ Z, int V_t,
+                                                                    int64_t ldz, int vec_store) {
+  constexpr int kKC = KC;               // hidden slice staged in LDS per barrier
+  constexpr int kKSteps = kKC / 32;     // MFMA steps per slice
+  constexpr int kLdsRow = kKC + 8;      // bf16 elements per padded LDS row: 16-byte reads of 16 rows hit 16 distinct bank groups
+  static_assert(kKSteps % PF == 0 && kGemmKPad % KC == 0, "prefetch depth must divide the steps per slice");
+  constexpr int kThreads = WPG * 64;
+  constexpr int kSliceVecs = MT * 16 * (kKC / 8);                     // 16-byte vectors per hidden slice
+  constexpr int kHLoads = (kSliceVecs + kThreads - 1) / kThreads;
+  __shared__ __attribute__((aligned(16))) uint16_t sH[2][MT * 16 * kLdsRow];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int wt = blockIdx.x * kWavesPerWG + wave;
+  const int wt = blockIdx.x * WPG + wave;
   const bool active = wt < n_wtiles;
   const int row0 = blockIdx.y * (MT * 16);
   const uint4* wp = Wp + ((int64_t)(active ? wt : 0) * nks) * 256 + lane;
@@ -76,40 +83,60 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(const uint16_t* __rest
 #pragma unroll
     for (int nw = 0; nw < 4; ++nw) bq[s][nw] = (active && s < nks) ? wp[(s * 4 + nw) * 64] : make_uint4(0, 0, 0, 0);
 
-  const int a_row = lane & 15, a_col = 8 * (lane >> 4);
-  for (int kc = 0; kc < nks; kc += kKSteps) {
-    __syncthreads();                       // the previous slice has been consumed
-    for (int idx = tid; idx < MT * 16 * (kKC / 8); idx += 256) {
+  uint4 hreg[kHLoads];
+  auto fetch_h = [&](int kc) {
+#pragma unroll
+    for (int i = 0; i < kHLoads; ++i) {
+      const int idx = tid + i * kThreads;
       const int r = idx / (kKC / 8), c = idx % (kKC / 8);
       const int gr = row0 + r, gk = kc * 32 + c * 8;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (gr < M && gk < d) v = *reinterpret_cast<const uint4*>(H + (int64_t)gr * d + gk);
-      *reinterpret_cast<uint4*>(&sH[r * kLdsRow + c * 8]) = v;
+      hreg[i] = make_uint4(0, 0, 0, 0);
+      if (idx < kSliceVecs && gr < M && gk < d) hreg[i] = *reinterpret_cast<const uint4*>(H + (int64_t)gr * d + gk);
     }
-    __syncthreads();
+  };
+  auto stash_h = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < kHLoads; ++i) {
+      const int idx = tid + i * kThreads;
+      const int r = idx / (kKC / 8), c = idx % (kKC / 8);
+      if (idx < kSliceVecs) *reinterpret_cast<uint4*>(&sH[buf][r * kLdsRow + c * 8]) = hreg[i];
+    }
+  };
+
+  fetch_h(0);
+  stash_h(0);
+  __syncthreads();
+  const int a_row = lane & 15, a_col = 8 * (lane >> 4);
+  int cur = 0;
+  for (int kc = 0; kc < nks; kc += kKSteps) {
+    const bool more = kc + kKSteps < nks;
+    if (more) fetch_h(kc + kKSteps);
     if (active) {
+      const uint16_t* hs = sH[cur];
 #pragma unroll
       for (int ks = 0; ks < kKSteps; ++ks) {
         const int kk = kc + ks;
-        uint4 bw[4];
 #pragma unroll
-        for (int nw = 0; nw < 4; ++nw) bw[nw] = bq[ks % PF][nw];
+        for (int mt = 0; mt < MT; ++mt) {
+          const uint4 hv = *reinterpret_cast<const uint4*>(&hs[(mt * 16 + a_row) * kLdsRow + ks * 32 + a_col]);
+          const bf16x8 hf = __builtin_bit_cast(bf16x8, hv);
+#pragma unroll
+          for (int nw = 0; nw < 4; ++nw) {
+            acc[mt][nw] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bq[ks % PF][nw]), hf,
+                                                                  acc[mt][nw], 0, 0, 0);
+          }
+        }
+        // the slot is free again: refill it with the fragments PF steps ahead
         if (kk + PF < nks) {
 #pragma unroll
           for (int nw = 0; nw < 4; ++nw) bq[ks % PF][nw] = wp[((int64_t)(kk + PF) * 4 + nw) * 64];
         }
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          const uint4 hv = *reinterpret_cast<const uint4*>(&sH[(mt * 16 + a_row) * kLdsRow + ks * 32 + a_col]);
-          const bf16x8 hf = __builtin_bit_cast(bf16x8, hv);
-#pragma unroll
-          for (int nw = 0; nw < 4; ++nw) {
-            acc[mt][nw] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bw[nw]), hf,
-                                                                  acc[mt][nw], 0, 0, 0);
-          }
-        }
+        __builtin_amdgcn_sched_barrier(0);   // keep the next step's LDS reads from being hoisted (register budget)
       }
     }
+    if (more) stash_h(cur ^ 1);
+    __syncthreads();
+    cur ^= 1;
   }
   if (!active) return;
   // lane holds Z[row0 + mt*16 + lane%16][wt*64 + nw*16 + 4*(lane/16) + 0..3]
@@ -132,6 +159,79 @@ __global__ __launch_bounds__(256) void lmhead_bf16_kernel(const uint16_t* __rest
   }
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// Skinny kernel: M <= 16 rows (one MFMA row tile).  A workgroup owns 64 columns and splits the hidden dimension
+// over its 8 wavefronts, so that even a 32000-column head yields thousands of wavefronts streaming W; the hidden
+// fragments are tiny and read straight from global memory (L2 resident).  The 8 partial tiles are summed through
+// LDS in a fixed order.
+template <int PF>
+__global__ __launch_bounds__(512) void lmhead_bf16_skinny_kernel(const uint16_t* __restrict__ H, int M, int d,
+                                                                 const uint4* __restrict__ Wp, int nks,
+                                                                 float* __restrict__ Z, int V_t, int64_t ldz) {
+  constexpr int kWaves = 8;
+  __shared__ __attribute__((aligned(16))) float sRed[kWaves][4][64][4];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int wt = blockIdx.x;
+  const int ks0 = (int)(((int64_t)nks * wave) / kWaves), ks1 = (int)(((int64_t)nks * (wave + 1)) / kWaves);
+  const uint4* wp = Wp + ((int64_t)wt * nks) * 256 + lane;
+  const int h_row = lane & 15, h_col = 8 * (lane >> 4);
+  const bool h_ok = h_row < M;
+  const uint16_t* hp = H + (int64_t)(h_ok ? h_row : 0) * d + h_col;
+
+  f32x4 acc[4];
+#pragma unroll
+  for (int nw = 0; nw < 4; ++nw) acc[nw] = f32x4{0.f, 0.f, 0.f, 0.f};
+  uint4 bq[PF][4], hq[PF];
+  auto fetch = [&](int slot, int ks) {
+#pragma unroll
+    for (int nw = 0; nw < 4; ++nw) bq[slot][nw] = wp[((int64_t)ks * 4 + nw) * 64];
+    hq[slot] = make_uint4(0, 0, 0, 0);
+    if (h_ok && ks * 32 + h_col < d) hq[slot] = *reinterpret_cast<const uint4*>(hp + ks * 32);
+  };
+#pragma unroll
+  for (int s = 0; s < PF; ++s) {
+    if (ks0 + s < ks1) fetch(s, ks0 + s);
+  }
+  for (int base = ks0; base < ks1; base += PF) {
+#pragma unroll
+    for (int s = 0; s < PF; ++s) {
+      const int ks = base + s;
+      if (ks < ks1) {
+        uint4 bw[4];
+#pragma unroll
+        for (int nw = 0; nw < 4; ++nw) bw[nw] = bq[s][nw];
+        const bf16x8 hf = __builtin_bit_cast(bf16x8, hq[s]);
+        if (ks + PF < ks1) fetch(s, ks + PF);
+#pragma unroll
+        for (int nw = 0; nw < 4; ++nw)
+          acc[nw] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bw[nw]), hf, acc[nw], 0, 0, 0);
+      }
+    }
+  }
+#pragma unroll
+  for (int nw = 0; nw < 4; ++nw)
+    *reinterpret_cast<float4*>(&sRed[wave][nw][lane][0]) = make_float4(acc[nw][0], acc[nw][1], acc[nw][2], acc[nw][3]);
+  __syncthreads();
+  if (tid < 256) {
+    const int nw = tid >> 6, l = tid & 63;
+    float4 sum = *reinterpret_cast<const float4*>(&sRed[0][nw][l][0]);
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) {
+      const float4 x = *reinterpret_cast<const float4*>(&sRed[w][nw][l][0]);
+      sum.x += x.x; sum.y += x.y; sum.z += x.z; sum.w += x.w;
+    }
+    const int m = l & 15;
+    const int n = wt * 64 + nw * 16 + 4 * (l >> 4);
+    if (m < M) {
+      float* dst = Z + (int64_t)m * ldz + n;
+      const float v[4] = {sum.x, sum.y, sum.z, sum.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (n + e < V_t) dst[e] = v[e];
+    }
+  }
+}
+
 // fp32 path (small fp32 problems only): one thread per logit, coalesced over the vocabulary.
 __global__ __launch_bounds__(256) void lmhead_f32_kernel(const float* __restrict__ H, int M, int d,
                                                          const float* __restrict__ W, float* __restrict__ Z, int V_t,
@@ -145,13 +245,13 @@ __global__ __launch_bounds__(256) void lmhead_f32_kernel(const float* __restrict
   Z[(int64_t)m * ldz + n] = acc;
 }
 
-template <int MT, int PF>
-hipError_t launch_one(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
-                      int64_t ldz, hipStream_t stream) {
+template <int MT, int PF, int WPG, int KC>
+hipError_t launch_wide(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
+                       int64_t ldz, hipStream_t stream) {
   const int nks = Kp / 32, n_wtiles = Vp / kGemmColsPerWave;
-  dim3 grid(ceil_div(n_wtiles, kWavesPerWG), ceil_div(M, MT * 16)), block(256);
+  dim3 grid(ceil_div(n_wtiles, WPG), ceil_div(M, MT * 16)), block(WPG * 64);
   const int vec_store = (ldz % 4 == 0) && (reinterpret_cast<uintptr_t>(Z) % 16 == 0);
-  hipLaunchKernelGGL((lmhead_bf16_kernel<MT, PF>), grid, block, 0, stream, H, M, d,
+  hipLaunchKernelGGL((lmhead_bf16_wide_kernel<MT, PF, WPG, KC>), grid, block, 0, stream, H, M, d,
                      reinterpret_cast<const uint4*>(Wp), nks, n_wtiles, Z, V_t, ldz, vec_store);
   return hipGetLastError();
 }
@@ -170,11 +270,16 @@ hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* W
                               int64_t ldz, hipStream_t stream) {
   if (M == 0) return hipSuccess;
   const int tiles = ceil_div(M, 16);
-  if (tiles <= 1) return launch_one<1, 4>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, stream);
-  if (tiles <= 3) return launch_one<3, 4>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, stream);
-  if (tiles <= 5) return launch_one<5, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, stream);
-  if (tiles <= 7) return launch_one<7, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, stream);
-  return launch_one<9, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, stream);
+  if (tiles <= 1) {
+    const int nks = Kp / 32, n_wtiles = Vp / kGemmColsPerWave;
+    hipLaunchKernelGGL((lmhead_bf16_skinny_kernel<4>), dim3(n_wtiles), dim3(512), 0, stream, H, M, d,
+                       reinterpret_cast<const uint4*>(Wp), nks, Z, V_t, ldz);
+    return hipGetLastError();
+  }
+  if (tiles <= 2) return launch_wide<2, 4, 4, 128>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, stream);
+  if (tiles <= 4) return launch_wide<4, 4, 4, 128>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, stream);
+  if (tiles <= 6) return launch_wide<6, 2, 8, 64>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, stream);
+  return launch_wide<9, 2, 8, 64>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, stream);
 }
 
 hipError_t launch_lmhead_f32(const float* H, int M, int d, const float* W, float* Z, int V_t, int64_t ldz,
