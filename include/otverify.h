@@ -18,8 +18,10 @@
  *   - Every function returns OT_OK (0) or a negative OT_ERR_*; nothing throws, aborts or prints.
  *     ot_last_error() returns a thread-local, NUL-terminated description of the last failure on this thread.
  *   - Pointers are marked HOST or DEVICE.  The library never frees or reallocates caller memory.
- *   - Device work is enqueued on the stream given at init and is asynchronous: the caller synchronises
- *     before reading outputs.  One context must not be used from two threads at once.
+ *   - Device work is enqueued on the stream given at init and is asynchronous: the caller synchronises that
+ *     stream before reading outputs.  (The draft-side kernels run on a second, internal stream that is forked
+ *     from and joined back into the caller's stream inside every step.)  One context must not be used from two
+ *     threads at once.
  *   - Uniform random numbers are Philox4x32-10 (Salmon et al., SC'11) with key = (seed low, seed high) and
  *     counter = (mapped position j, step, seq_id low, seq_id high).  Output word 0 gives the acceptance
  *     uniform of position j, word 1 the uniform of the final-token draw at row j; a uniform is the word's top
@@ -156,11 +158,12 @@ typedef struct ot_workspace_view {
 } ot_workspace_view;
 int ot_verify_workspace(ot_ctx* ctx, ot_workspace_view* view);
 
-/* Kernel timing.  While enabled, every step records HIP events between its kernels on the context's stream.
+/* Kernel timing.  While enabled, every step records HIP events around its kernels on the streams they run on
+ * (the two draft-side kernels run on an internal side stream, concurrently with the LM head).
  * ot_verify_profile_read synchronises the stream, adds the elapsed milliseconds of the steps run since the
  * last read into ms[0 .. OT_N_STAGES) (overwriting it), stores the number of steps in *n_steps and resets.    */
-#define OT_STAGE_DRAFT_STATS   0   /* softmax statistics of the draft rows                                    */
-#define OT_STAGE_MAP           1   /* translation scan and n-gram cache probes (Eq. 1)                        */
+#define OT_STAGE_DRAFT_STATS   0   /* softmax statistics of the draft rows (side stream)                      */
+#define OT_STAGE_MAP           1   /* translation scan and n-gram cache probes, Eq. 1 (side stream)           */
 #define OT_STAGE_LM_HEAD       2   /* z = h . W                                                               */
 #define OT_STAGE_TARGET_STATS  3   /* softmax statistics of the target rows                                   */
 #define OT_STAGE_ACCEPT        4   /* acceptance ratios, Philox uniforms, first rejection                     */

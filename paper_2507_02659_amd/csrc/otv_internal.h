@@ -11,7 +11,7 @@ namespace otv {
 // ------------------------------------------------------------------------------------------------ geometry
 constexpr int kStatThreads = 256;
 constexpr int kStatChunk = 4096;     // logits per workgroup of the softmax-statistics kernel
-constexpr int kResidTile = 4096;     // vocabulary entries per workgroup of the residual kernels
+constexpr int kResidTile = 1024;     // vocabulary entries per workgroup of the residual kernel
 constexpr int kGemmColsPerWave = 64; // LM-head columns owned by one wavefront
 constexpr int kGemmKPad = 128;       // packed K extent is a multiple of this
 
@@ -93,8 +93,9 @@ hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* W
                               int64_t ldz, hipStream_t stream);
 hipError_t launch_lmhead_f32(const float* H, int M, int d, const float* W, float* Z, int V_t, int64_t ldz,
                              hipStream_t stream);
-hipError_t launch_stats(const StepArgs& a, bool draft, hipStream_t stream);
+hipError_t launch_draft_stats(const StepArgs& a, hipStream_t stream);
 hipError_t launch_map(const StepArgs& a, hipStream_t stream);
+hipError_t launch_target_stats(const StepArgs& a, hipStream_t stream);
 hipError_t launch_accept(const StepArgs& a, hipStream_t stream);
 hipError_t launch_resid_sums(const StepArgs& a, hipStream_t stream);
 hipError_t launch_resid_pick(const StepArgs& a, hipStream_t stream);
