@@ -39,6 +39,7 @@ struct ot_ctx {
   int device = 0;
   std::vector<void*> allocs;
   uint16_t* Wp = nullptr;
+  uint16_t* zeros = nullptr;          // 64 zero bytes: source of the K tail in the LM-head's hidden slices
   float* Wf = nullptr;
   int32_t *dmap = nullptr, *tmap = nullptr;
   float* Z = nullptr;
@@ -141,7 +142,7 @@ int ot_verify_init(const ot_verify_config* cfg, ot_ctx** out) {
 
   const size_t R = (size_t)c->max_rows, KQ = (size_t)c->max_K, Bm = (size_t)c->max_batch;
   bool ok = true;
-  if (c->dtype == OT_BF16) ok = ok && dev_alloc(c, &c->Wp, (size_t)c->Kp * c->Vp);
+  if (c->dtype == OT_BF16) ok = ok && dev_alloc(c, &c->Wp, (size_t)c->Kp * c->Vp) && dev_alloc(c, &c->zeros, 32);
   else ok = ok && dev_alloc(c, &c->Wf, (size_t)c->d * c->V_t);
   ok = ok && dev_alloc(c, &c->dmap, (size_t)c->V_d) && dev_alloc(c, &c->tmap, (size_t)c->V_t);
   ok = ok && dev_alloc(c, &c->Z, R * (size_t)c->V_t);
@@ -157,6 +158,7 @@ int ot_verify_init(const ot_verify_config* cfg, ot_ctx** out) {
   e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&c->fork, hipEventDisableTiming);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&c->join, hipEventDisableTiming);
+  if (e == hipSuccess && c->zeros) e = hipMemsetAsync(c->zeros, 0, 64, c->stream);
   if (e == hipSuccess) e = hipMemcpyAsync(c->dmap, cfg->direct_map, sizeof(int32_t) * c->V_d, hipMemcpyHostToDevice, c->stream);
   if (e == hipSuccess) e = hipMemcpyAsync(c->tmap, tmap_h.data(), sizeof(int32_t) * c->V_t, hipMemcpyHostToDevice, c->stream);
   if (e == hipSuccess) {
@@ -311,7 +313,7 @@ static int step_impl(ot_ctx* ctx, const ot_ngram_cache* cache, const ot_step_in*
   if (e == hipSuccess && !from_logits) {
     if (ctx->dtype == OT_BF16)
       e = launch_lmhead_bf16(static_cast<const uint16_t*>(in->hidden), M, ctx->d, ctx->Wp, ctx->Kp, ctx->Vp, ctx->Z,
-                             ctx->V_t, a.ldz, st);
+                             ctx->V_t, a.ldz, ctx->zeros, st);
     else
       e = launch_lmhead_f32(static_cast<const float*>(in->hidden), M, ctx->d, ctx->Wf, ctx->Z, ctx->V_t, a.ldz, st);
   }

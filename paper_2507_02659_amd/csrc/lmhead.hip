@@ -9,9 +9,11 @@
 //     with fully coalesced 16-byte loads straight into MFMA operand registers: no LDS round trip, no transpose.
 //   * Every weight is used by exactly one wavefront, which keeps accumulators for ALL rows of the M-block
 //     (up to 9 x 16 rows x 64 columns = 144 registers), so W never has to be re-read for another row tile.
-//   * The hidden rows, shared by the four wavefronts of a workgroup, are staged through LDS in 128-deep slices
-//     (padded rows: conflict-free 16-byte reads); each hidden fragment read from LDS feeds four MFMAs.
-//   * Weight fragments are prefetched kPrefetch steps ahead in registers to keep enough bytes in flight.
+//   * The hidden rows, shared by the wavefronts of a workgroup, go through LDS in 128-deep double-buffered slices
+//     filled by direct global->LDS loads (swizzled rows: conflict-free 16-byte reads); each hidden fragment read
+//     from LDS feeds four MFMAs.
+//   * Weight fragments are prefetched PF 32-deep steps ahead in registers, so that the one barrier per slice never
+//     waits on HBM latency.
 // Operand roles: the weight fragment is MFMA operand A and the hidden fragment operand B, so a lane ends up with
 // four consecutive vocabulary columns of one row and stores them as one float4.
 #include "otv_internal.h"
@@ -50,21 +52,31 @@ __global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict_
 
 // ---------------------------------------------------------------------------------------------------------------
 // Wide kernel: M-blocks of up to MT*16 rows.  WPG wavefronts per workgroup, each owning 64 columns over the whole
-// hidden dimension; the hidden slice is double-buffered in LDS (next slice fetched into registers while the current
-// one feeds the MFMAs, written to the other buffer afterwards: one barrier per slice).
+// hidden dimension.  The hidden slice (KC columns of all rows of the M-block) is double-buffered in LDS and filled
+// by direct global->LDS loads (no staging registers): the next slice is requested before the current one feeds the
+// MFMAs, and one barrier per slice hands the buffers over.  LDS rows are unpadded; the 16-byte chunks of a row are
+// XOR-swizzled with the row index (applied on the global side of the copy, since a direct load writes consecutive
+// lanes to consecutive LDS addresses) so that the 16 rows a fragment read touches fall into 16 distinct bank groups.
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* glb_ptr_t;
+
+// s_waitcnt immediate (gfx9 encoding) that waits until at most N vector-memory loads are outstanding and nothing else
+constexpr int vmcnt_imm(int n) { return (n & 0xF) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
+
 template <int MT, int PF, int WPG, int KC>
 __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16_t* __restrict__ H, int M, int d,
                                                                     const uint4* __restrict__ Wp, int nks,
                                                                     int n_wtiles, float* __restrict__ Z, int V_t,
-                                                                    int64_t ldz, int vec_store) {
-  constexpr int kKC = KC;               // hidden slice staged in LDS per barrier
-  constexpr int kKSteps = kKC / 32;     // MFMA steps per slice
-  constexpr int kLdsRow = kKC + 8;      // bf16 elements per padded LDS row: 16-byte reads of 16 rows hit 16 distinct bank groups
-  static_assert(kKSteps % PF == 0 && kGemmKPad % KC == 0, "prefetch depth must divide the steps per slice");
-  constexpr int kThreads = WPG * 64;
-  constexpr int kSliceVecs = MT * 16 * (kKC / 8);                     // 16-byte vectors per hidden slice
-  constexpr int kHLoads = (kSliceVecs + kThreads - 1) / kThreads;
-  __shared__ __attribute__((aligned(16))) uint16_t sH[2][MT * 16 * kLdsRow];
+                                                                    int64_t ldz, int vec_store,
+                                                                    const uint16_t* __restrict__ zeros) {
+  constexpr int kKSteps = KC / 32;                 // MFMA steps per slice
+  constexpr int kCPR = KC / 8;                     // 16-byte chunks per slice row
+  constexpr int kSliceChunks = MT * 16 * kCPR;
+  constexpr int kDma = (kSliceChunks + WPG * 64 - 1) / (WPG * 64);
+  static_assert(kKSteps % PF == 0 && kGemmKPad % KC == 0 && kCPR >= 16 && kKSteps * 4 < 64, "slice geometry");
+  __shared__ __attribute__((aligned(16))) uint16_t sA[MT * 16 * KC];
+  __shared__ __attribute__((aligned(16))) uint16_t sB[MT * 16 * KC];
+  __shared__ __attribute__((aligned(16))) float sPatch[WPG][16 * 68];   // epilogue: one 16 x 64 tile per wavefront
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wt = blockIdx.x * WPG + wave;
   const bool active = wt < n_wtiles;
@@ -77,83 +89,104 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
 #pragma unroll
     for (int nw = 0; nw < 4; ++nw) acc[mt][nw] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  // request slice kc (in 32-column steps) into buffer s: chunk q of the buffer holds logical chunk (q%kCPR)^(row&15)
+  auto request = [&](int kc, uint16_t* s) {
+#pragma unroll
+    for (int j = 0; j < kDma; ++j) {
+      const int q0 = (j * WPG + wave) * 64;        // wave-uniform
+      if (q0 < kSliceChunks) {
+        const int q = q0 + lane;
+        const int row = q / kCPR, pc = q % kCPR;
+        const int lc = pc ^ (row & 15);
+        const int gr = min(row0 + row, M - 1);     // rows past M are never stored: any valid row will do
+        const int gk = kc * 32 + lc * 8;
+        const uint16_t* src = gk < d ? H + (int64_t)gr * d + gk : zeros;   // the padded tail of K must read as zero
+        __builtin_amdgcn_global_load_lds((glb_ptr_t)src, (lds_ptr_t)(s + q0 * 8), 16, 0, 0);
+      }
+    }
+  };
+
+  request(0, sA);
   uint4 bq[PF][4];
 #pragma unroll
   for (int s = 0; s < PF; ++s)
 #pragma unroll
     for (int nw = 0; nw < 4; ++nw) bq[s][nw] = (active && s < nks) ? wp[(s * 4 + nw) * 64] : make_uint4(0, 0, 0, 0);
-
-  uint4 hreg[kHLoads];
-  auto fetch_h = [&](int kc) {
-#pragma unroll
-    for (int i = 0; i < kHLoads; ++i) {
-      const int idx = tid + i * kThreads;
-      const int r = idx / (kKC / 8), c = idx % (kKC / 8);
-      const int gr = row0 + r, gk = kc * 32 + c * 8;
-      hreg[i] = make_uint4(0, 0, 0, 0);
-      if (idx < kSliceVecs && gr < M && gk < d) hreg[i] = *reinterpret_cast<const uint4*>(H + (int64_t)gr * d + gk);
-    }
-  };
-  auto stash_h = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < kHLoads; ++i) {
-      const int idx = tid + i * kThreads;
-      const int r = idx / (kKC / 8), c = idx % (kKC / 8);
-      if (idx < kSliceVecs) *reinterpret_cast<uint4*>(&sH[buf][r * kLdsRow + c * 8]) = hreg[i];
-    }
-  };
-
-  fetch_h(0);
-  stash_h(0);
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
   __syncthreads();
-  const int a_row = lane & 15, a_col = 8 * (lane >> 4);
-  int cur = 0;
-  for (int kc = 0; kc < nks; kc += kKSteps) {
-    const bool more = kc + kKSteps < nks;
-    if (more) fetch_h(kc + kKSteps);
-    if (active) {
-      const uint16_t* hs = sH[cur];
+
+  const int a_row = lane & 15, a_grp = lane >> 4;
+  auto compute = [&](const uint16_t* hs, int kc) {
+    if (!active) return;
 #pragma unroll
-      for (int ks = 0; ks < kKSteps; ++ks) {
-        const int kk = kc + ks;
+    for (int ks = 0; ks < kKSteps; ++ks) {
+      const int kk = kc + ks;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          const uint4 hv = *reinterpret_cast<const uint4*>(&hs[(mt * 16 + a_row) * kLdsRow + ks * 32 + a_col]);
-          const bf16x8 hf = __builtin_bit_cast(bf16x8, hv);
+      for (int mt = 0; mt < MT; ++mt) {
+        const int pc = (ks * 4 + a_grp) ^ a_row;
+        const uint4 hv = *reinterpret_cast<const uint4*>(&hs[(mt * 16 + a_row) * KC + pc * 8]);
+        const bf16x8 hf = __builtin_bit_cast(bf16x8, hv);
 #pragma unroll
-          for (int nw = 0; nw < 4; ++nw) {
-            acc[mt][nw] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bq[ks % PF][nw]), hf,
-                                                                  acc[mt][nw], 0, 0, 0);
-          }
+        for (int nw = 0; nw < 4; ++nw) {
+          acc[mt][nw] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bq[ks % PF][nw]), hf,
+                                                                acc[mt][nw], 0, 0, 0);
         }
-        // the slot is free again: refill it with the fragments PF steps ahead
-        if (kk + PF < nks) {
-#pragma unroll
-          for (int nw = 0; nw < 4; ++nw) bq[ks % PF][nw] = wp[((int64_t)(kk + PF) * 4 + nw) * 64];
-        }
-        __builtin_amdgcn_sched_barrier(0);   // keep the next step's LDS reads from being hoisted (register budget)
       }
+      // the slot is free again: refill it with the fragments PF steps ahead
+      if (kk + PF < nks) {
+#pragma unroll
+        for (int nw = 0; nw < 4; ++nw) bq[ks % PF][nw] = wp[((int64_t)(kk + PF) * 4 + nw) * 64];
+      }
+      __builtin_amdgcn_sched_barrier(0);   // keep the next step's LDS reads from being hoisted (register budget)
     }
-    if (more) stash_h(cur ^ 1);
+  };
+  // Loads complete in issue order, so once at most kKSteps*4 loads (the weight fragments requested during the slice)
+  // are outstanding, this wavefront's part of the next hidden slice has landed in LDS.
+  auto hand_over = [&](int kc) {
+    __builtin_amdgcn_sched_barrier(0);
+    if (active && kc + kKSteps - 1 + PF < nks) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kKSteps * 4));
+    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __syncthreads();
-    cur ^= 1;
+  };
+
+  for (int kc = 0; kc < nks; kc += 2 * kKSteps) {
+    const bool more = kc + kKSteps < nks;
+    if (more) request(kc + kKSteps, sB);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(sA, kc);
+    hand_over(kc);
+    if (!more) break;
+    if (kc + 2 * kKSteps < nks) request(kc + 2 * kKSteps, sA);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(sB, kc + kKSteps);
+    hand_over(kc + kKSteps);
   }
   if (!active) return;
-  // lane holds Z[row0 + mt*16 + lane%16][wt*64 + nw*16 + 4*(lane/16) + 0..3]
+  // Epilogue.  After the MFMAs a lane holds Z[row0 + mt*16 + lane%16][wt*64 + nw*16 + 4*(lane/16) + 0..3]: 64-byte
+  // pieces of 16 rows per store.  Each 16 x 64 tile is turned through a wave-private LDS patch (rows padded to 68
+  // floats) so that a store instruction writes 4 rows x 256 contiguous bytes, and the logits are written with
+  // nontemporal stores: they are not re-read by this kernel and should not evict the weight stream.
+  float* patch = sPatch[wave];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    const int m = row0 + mt * 16 + (lane & 15);
-    if (m >= M) continue;
 #pragma unroll
-    for (int nw = 0; nw < 4; ++nw) {
-      const int n = wt * 64 + nw * 16 + 4 * (lane >> 4);
-      float* dst = Z + (int64_t)m * ldz + n;
-      if (vec_store && n + 3 < V_t) {
-        *reinterpret_cast<float4*>(dst) = make_float4(acc[mt][nw][0], acc[mt][nw][1], acc[mt][nw][2], acc[mt][nw][3]);
-      } else {
+    for (int nw = 0; nw < 4; ++nw)
+      *reinterpret_cast<f32x4*>(&patch[(lane & 15) * 68 + nw * 16 + 4 * (lane >> 4)]) = acc[mt][nw];
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-          if (n + e < V_t) dst[e] = acc[mt][nw][e];
+    for (int i = 0; i < 4; ++i) {
+      const int r = (lane >> 4) + 4 * i;
+      const f32x4 v = *reinterpret_cast<const f32x4*>(&patch[r * 68 + 4 * (lane & 15)]);
+      const int m = row0 + mt * 16 + r;
+      const int n = wt * 64 + 4 * (lane & 15);
+      if (m < M) {
+        float* dst = Z + (int64_t)m * ldz + n;
+        if (vec_store && n + 3 < V_t) {
+          __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst));
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (n + e < V_t) dst[e] = v[e];
+        }
       }
     }
   }
@@ -247,12 +280,12 @@ __global__ __launch_bounds__(256) void lmhead_f32_kernel(const float* __restrict
 
 template <int MT, int PF, int WPG, int KC>
 hipError_t launch_wide(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
-                       int64_t ldz, hipStream_t stream) {
+                       int64_t ldz, const uint16_t* zeros, hipStream_t stream) {
   const int nks = Kp / 32, n_wtiles = Vp / kGemmColsPerWave;
   dim3 grid(ceil_div(n_wtiles, WPG), ceil_div(M, MT * 16)), block(WPG * 64);
   const int vec_store = (ldz % 4 == 0) && (reinterpret_cast<uintptr_t>(Z) % 16 == 0);
   hipLaunchKernelGGL((lmhead_bf16_wide_kernel<MT, PF, WPG, KC>), grid, block, 0, stream, H, M, d,
-                     reinterpret_cast<const uint4*>(Wp), nks, n_wtiles, Z, V_t, ldz, vec_store);
+                     reinterpret_cast<const uint4*>(Wp), nks, n_wtiles, Z, V_t, ldz, vec_store, zeros);
   return hipGetLastError();
 }
 
@@ -267,7 +300,7 @@ hipError_t launch_pack_w_bf16(const uint16_t* W, int d, int V_t, uint16_t* Wp, i
 }
 
 hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
-                              int64_t ldz, hipStream_t stream) {
+                              int64_t ldz, const uint16_t* zeros, hipStream_t stream) {
   if (M == 0) return hipSuccess;
   const int tiles = ceil_div(M, 16);
   if (tiles <= 1) {
@@ -276,10 +309,10 @@ hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* W
                        reinterpret_cast<const uint4*>(Wp), nks, Z, V_t, ldz);
     return hipGetLastError();
   }
-  if (tiles <= 2) return launch_wide<2, 4, 4, 128>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, stream);
-  if (tiles <= 4) return launch_wide<4, 4, 4, 128>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, stream);
-  if (tiles <= 6) return launch_wide<6, 2, 8, 64>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, stream);
-  return launch_wide<9, 2, 8, 64>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, stream);
+  if (tiles <= 2) return launch_wide<2, 4, 4, 128>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
+  if (tiles <= 4) return launch_wide<4, 4, 4, 128>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
+  if (tiles <= 6) return launch_wide<6, 4, 4, 128>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
+  return launch_wide<9, 4, 4, 128>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
 }
 
 hipError_t launch_lmhead_f32(const float* H, int M, int d, const float* W, float* Z, int V_t, int64_t ldz,

@@ -90,7 +90,7 @@ struct StepArgs {
 // Each returns the hipError_t of its launch.  All work goes to `stream`.
 hipError_t launch_pack_w_bf16(const uint16_t* W, int d, int V_t, uint16_t* Wp, int Kp, int Vp, hipStream_t stream);
 hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
-                              int64_t ldz, hipStream_t stream);
+                              int64_t ldz, const uint16_t* zeros, hipStream_t stream);
 hipError_t launch_lmhead_f32(const float* H, int M, int d, const float* W, float* Z, int V_t, int64_t ldz,
                              hipStream_t stream);
 hipError_t launch_draft_stats(const StepArgs& a, hipStream_t stream);
