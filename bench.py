@@ -48,6 +48,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=4, help="BASELINE configuration 1..5 (default: the headline one)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (known HBM traffic) so that a rocprofv3 --pmc run of this "
+                         "command can scale FETCH_SIZE / WRITE_SIZE of the LM-head kernel against it")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU (no sharding, no collectives); run with --gpus 1")
@@ -60,6 +63,14 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the verification path has no CPU fallback")
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()     # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     t0 = time.time()
     case = make_case(baseline_spec(args.config))

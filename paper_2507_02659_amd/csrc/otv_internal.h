@@ -41,15 +41,19 @@ __host__ __device__ inline uint32_t hash_ngram(const int32_t* ids, int len) {
 // ------------------------------------------------------------------------------------------------ per-step view
 // What the final-token kernels need to know about sequence b; written by the acceptance kernel.
 struct FinalInfo {
-  int32_t mode;     // 0: nothing to draw (greedy, or bad id), 2: draw from p (free token), 3: draw from the residual
-  int32_t row;      // global row of the final token (row_off[b] + n_b)
-  int32_t drow;     // global draft row whose distribution fills Eq. 2's "otherwise" branch
-  int32_t t_ng;     // target id of the n-gram matched at the rejected position, or -1
-  int32_t t_pre;    // direct image of that n-gram's first sub-token, or -1
+  int32_t mode;          // 0: nothing to draw (greedy, or bad id), 2: draw from p (free token), 3: draw from the residual
+  int32_t row;           // global row of the final token (row_off[b] + n_b)
+  int32_t drow;          // global draft row whose distribution fills Eq. 2's "otherwise" branch
+  int32_t t_ng;          // target id of the n-gram matched at the rejected position, or -1
+  int32_t t_pre;         // direct image of that n-gram's first sub-token, or -1
+  int32_t argq;          // argmax of the draft row (used when the draft temperature is 0)
+  int32_t greedy_draft;  // draft temperature is 0: q is one-hot at argq
   int32_t pad;
-  double pi;        // product of the n-gram's sub-token probabilities
-  double q_pre;     // q(d_1) - pi
-  double u2;        // uniform of the draw
+  double pi;             // product of the n-gram's sub-token probabilities
+  double q_pre;          // q(d_1) - pi
+  double u2;             // uniform of the draw
+  // p(v) = exp((z_v - mx) * invT) * invS at the final row; q_s(d) = exp((zq_d - mxq) * invTd) * invSq at draft row drow
+  double mx, invT, invS, mxq, invTd, invSq;
 };
 
 struct StepArgs {

@@ -50,44 +50,39 @@ struct FinalRow {
   }
 };
 
-__device__ inline FinalRow make_final_row(const StepArgs& a, int b, const FinalInfo& f) {
+__device__ inline FinalRow make_final_row(const StepArgs& a, const FinalInfo& f) {
   FinalRow R;
-  const float T = a.temperature[b];
   R.z = a.Z + (int64_t)f.row * a.ldz;
-  R.mx = (double)a.row_max[f.row];
-  R.invT = 1.0 / (double)T;
-  R.invS = 1.0 / a.row_sum[f.row];
+  R.mx = f.mx; R.invT = f.invT; R.invS = f.invS;
   R.residual = f.mode == 3;
   R.dtype = a.dtype;
   R.tmap = a.tmap;
   R.t_ng = f.t_ng; R.t_pre = f.t_pre; R.pi = f.pi; R.q_pre = f.q_pre;
-  R.zq = nullptr; R.mxq = 0.0; R.invTd = 1.0; R.invSq = 1.0; R.argq = -1; R.greedy_draft = false;
-  if (R.residual) {
-    const float Td = a.draft_temperature ? a.draft_temperature[b] : T;
-    const size_t esz = a.dtype == OT_BF16 ? 2 : 4;
-    R.zq = static_cast<const char*>(a.draft_logits) + (size_t)f.drow * a.V_d * esz;
-    R.mxq = (double)a.drow_max[f.drow];
-    R.greedy_draft = !(Td > 0.f);
-    R.invTd = R.greedy_draft ? 1.0 : 1.0 / (double)Td;
-    R.invSq = 1.0 / a.drow_sum[f.drow];
-    R.argq = a.drow_arg[f.drow];
-  }
+  R.zq = static_cast<const char*>(a.draft_logits) + (size_t)f.drow * a.V_d * (a.dtype == OT_BF16 ? 2 : 4);
+  R.mxq = f.mxq; R.invTd = f.invTd; R.invSq = f.invSq; R.argq = f.argq; R.greedy_draft = f.greedy_draft != 0;
   return R;
 }
 
+// Inverse direct map of kPer ids v = first + e * stride (independent of which row is drawn from: issued early).
+__device__ inline void load_tmap(const int32_t* __restrict__ tmap, int V_t, int first, int stride, int* dv) {
+#pragma unroll
+  for (int e = 0; e < kPer; ++e) {
+    const int v = first + e * stride;
+    dv[e] = v < V_t ? tmap[v] : -1;
+  }
+}
+
 // Residual mass r(v) and p(v) for kPer ids v = first + e * stride.  All loads are issued before any arithmetic.
-__device__ inline void tile_values(const FinalRow& R, int V_t, int first, int stride, double* r, double* p) {
+__device__ inline void tile_values(const FinalRow& R, int V_t, int first, int stride, const int* dv, double* r,
+                                   double* p) {
   float zv[kPer];
-  int dv[kPer];
   float xq[kPer];
 #pragma unroll
   for (int e = 0; e < kPer; ++e) {
     const int v = first + e * stride;
     zv[e] = v < V_t ? R.z[v] : -INFINITY;
-    dv[e] = (R.residual && v < V_t) ? R.tmap[v] : -1;
+    xq[e] = (R.residual && dv[e] >= 0 && !R.greedy_draft) ? R.draft_logit(dv[e]) : 0.f;
   }
-#pragma unroll
-  for (int e = 0; e < kPer; ++e) xq[e] = (dv[e] >= 0 && !R.greedy_draft) ? R.draft_logit(dv[e]) : 0.f;
 #pragma unroll
   for (int e = 0; e < kPer; ++e) {
     const int v = first + e * stride;
@@ -99,15 +94,17 @@ __device__ inline void tile_values(const FinalRow& R, int V_t, int first, int st
 __global__ __launch_bounds__(kThreads) void resid_sums_kernel(StepArgs a) {
   const int b = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
+  int dv[kPer];
+  load_tmap(a.tmap, a.V_t, tile * kResidTile + tid, kThreads, dv);     // does not depend on the row: overlaps the next load
   const FinalInfo f = a.fin[b];
   if (f.mode == 0) return;                  // greedy or flagged sequence: nothing to draw
-  const FinalRow R = make_final_row(a, b, f);
+  const FinalRow R = make_final_row(a, f);
   __shared__ double s_w[2][kThreads / 64];
 
   // ---- mass of this tile (coalesced: consecutive threads on consecutive ids)
   {
     double r[kPer], p[kPer];
-    tile_values(R, a.V_t, tile * kResidTile + tid, kThreads, r, p);
+    tile_values(R, a.V_t, tile * kResidTile + tid, kThreads, dv, r, p);
     double sr = (r[0] + r[1]) + (r[2] + r[3]);
     double sp = (p[0] + p[1]) + (p[2] + p[3]);
 #pragma unroll
@@ -126,7 +123,7 @@ __global__ __launch_bounds__(kThreads) void resid_pick_kernel(StepArgs a) {
   const int wave = tid >> 6, lane = tid & 63;
   const FinalInfo f = a.fin[b];
   if (f.mode == 0) return;
-  FinalRow R = make_final_row(a, b, f);
+  FinalRow R = make_final_row(a, f);
   __shared__ double s_w[2][kThreads / 64];
   extern __shared__ double s_tiles[];       // [2][ntiles]: residual masses, then p masses
   __shared__ int s_pick, s_fallback, s_first, s_lastnz;
@@ -196,7 +193,9 @@ __global__ __launch_bounds__(kThreads) void resid_pick_kernel(StepArgs a) {
   const double target = s_target;
   const int v0 = s_pick * kResidTile + tid * kPer;       // thread owns kPer consecutive ids: ascending running sum
   double r[kPer], p[kPer];
-  tile_values(R, a.V_t, v0, 1, r, p);
+  int dv[kPer];
+  load_tmap(a.tmap, a.V_t, v0, 1, dv);
+  tile_values(R, a.V_t, v0, 1, dv, r, p);
   const double local = ((r[0] + r[1]) + r[2]) + r[3];
   double incl = local;                                   // inclusive scan over the wavefront, fixed order
 #pragma unroll

@@ -194,8 +194,9 @@ __global__ __launch_bounds__(256) void accept_kernel(StepArgs a) {
   const int arg = lane <= k ? s_arg[lane] : 0;
 
   FinalInfo fin;
-  fin.mode = 0; fin.row = r0; fin.drow = 0; fin.t_ng = -1; fin.t_pre = -1; fin.pad = 0;
-  fin.pi = 0.0; fin.q_pre = 0.0; fin.u2 = 0.0;
+  fin.mode = 0; fin.row = r0; fin.drow = 0; fin.t_ng = -1; fin.t_pre = -1; fin.argq = -1; fin.greedy_draft = 0;
+  fin.pad = 0; fin.pi = 0.0; fin.q_pre = 0.0; fin.u2 = 0.0;
+  fin.mx = 0.0; fin.invT = 1.0; fin.invS = 1.0; fin.mxq = 0.0; fin.invTd = 1.0; fin.invSq = 1.0;
 
   if (flags & OT_FLAG_BAD_ID) {
     if (lane <= k) {
@@ -254,6 +255,8 @@ __global__ __launch_bounds__(256) void accept_kernel(StepArgs a) {
   const int fin_L = __shfl(L_j, n);
   const int fin_t = __shfl(t_j, n);
   const double fin_qp = __shfl(qp, n);
+  const float fin_mx = __shfl(mx, n);
+  const double fin_S = __shfl(S, n);
   if (lane == 0) {
     a.out.n_accept[b] = n;
     a.out.n_accept_draft[b] = len_acc;
@@ -264,6 +267,7 @@ __global__ __launch_bounds__(256) void accept_kernel(StepArgs a) {
       uint32_t w[4];
       philox4x32_10((uint32_t)n, a.step, (uint32_t)sid, (uint32_t)(sid >> 32), k0, k1, w);
       fin.u2 = u24(w[1]);
+      fin.mx = (double)fin_mx; fin.invT = invT; fin.invS = 1.0 / fin_S;
       const bool unmappable = (flags & OT_FLAG_UNMAPPABLE) != 0;
       if (n == m && !unmappable) {
         fin.mode = 2;
@@ -271,6 +275,12 @@ __global__ __launch_bounds__(256) void accept_kernel(StepArgs a) {
         fin.mode = 3;
         const int s = (n < m) ? fin_span_s : a.s_end[b];
         fin.drow = q0 + s;
+        const float Td = a.draft_temperature ? a.draft_temperature[b] : T;
+        fin.greedy_draft = !(Td > 0.f);
+        fin.invTd = fin.greedy_draft ? 1.0 : 1.0 / (double)Td;
+        fin.mxq = (double)a.drow_max[q0 + s];
+        fin.invSq = 1.0 / a.drow_sum[q0 + s];
+        fin.argq = a.drow_arg[q0 + s];
         if (n < m && fin_L > 1) {
           const int d1 = a.draft_ids[q0 + s];
           fin.t_ng = fin_t;
