@@ -68,7 +68,7 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
                                                                     const uint4* __restrict__ Wp, int nks,
                                                                     int n_wtiles, float* __restrict__ Z, int V_t,
                                                                     int64_t ldz, int vec_store,
-                                                                    const uint16_t* __restrict__ zeros) {
+                                                                    const uint16_t* __restrict__ zeros, int m_blocks) {
   constexpr int kKSteps = KC / 32;                 // MFMA steps per slice
   constexpr int kCPR = KC / 8;                     // 16-byte chunks per slice row
   constexpr int kSliceChunks = MT * 16 * kCPR;
@@ -78,9 +78,15 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
   __shared__ __attribute__((aligned(16))) uint16_t sB[MT * 16 * KC];
   __shared__ __attribute__((aligned(16))) float sPatch[WPG][16 * 68];   // epilogue: one 16 x 64 tile per wavefront
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int wt = blockIdx.x * WPG + wave;
+  // Workgroup id -> (column tile, M-block).  Consecutive ids go round-robin to the 8 XCDs, each with its own L2; the
+  // M-blocks of one column tile get ids that land on the same XCD back to back, so that when M needs several
+  // blocks their weight streams coincide in that XCD's L2 and HBM is still read once.
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int col_tile = (slot / m_blocks) * 8 + xcd, m_block = slot % m_blocks;
+  const int wt = col_tile * WPG + wave;
+  if (col_tile * WPG >= n_wtiles) return;            // padding of the id space (whole workgroup)
   const bool active = wt < n_wtiles;
-  const int row0 = blockIdx.y * (MT * 16);
+  const int row0 = m_block * (MT * 16);
   const uint4* wp = Wp + ((int64_t)(active ? wt : 0) * nks) * 256 + lane;
 
   f32x4 acc[MT][4];
@@ -282,10 +288,11 @@ template <int MT, int PF, int WPG, int KC>
 hipError_t launch_wide(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
                        int64_t ldz, const uint16_t* zeros, hipStream_t stream) {
   const int nks = Kp / 32, n_wtiles = Vp / kGemmColsPerWave;
-  dim3 grid(ceil_div(n_wtiles, WPG), ceil_div(M, MT * 16)), block(WPG * 64);
+  const int m_blocks = ceil_div(M, MT * 16);
+  dim3 grid(ceil_div(ceil_div(n_wtiles, WPG), 8) * 8 * m_blocks), block(WPG * 64);
   const int vec_store = (ldz % 4 == 0) && (reinterpret_cast<uintptr_t>(Z) % 16 == 0);
   hipLaunchKernelGGL((lmhead_bf16_wide_kernel<MT, PF, WPG, KC>), grid, block, 0, stream, H, M, d,
-                     reinterpret_cast<const uint4*>(Wp), nks, n_wtiles, Z, V_t, ldz, vec_store, zeros);
+                     reinterpret_cast<const uint4*>(Wp), nks, n_wtiles, Z, V_t, ldz, vec_store, zeros, m_blocks);
   return hipGetLastError();
 }
 
