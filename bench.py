@@ -109,15 +109,15 @@ def main():
     gemm_bytes = lm_head_bytes(M, d, V_t) if esz == 2 else 4 * d * V_t + 4 * M * d + 4 * M * V_t
     gemm_s = stage_us["lm_head"] * 1e-6
     achieved = gemm_bytes / gemm_s / 1e9 if gemm_s > 0 else 0.0
-    stats_bytes = 4 * M * V_t
+    stats_bytes = 4 * M * V_t + esz * K * V_d          # one pass over the target logits and the draft logits
     extra = {
         "stage_us": {k: round(x, 2) for k, x in stage_us.items()},
         "lm_head_tflops": round(2.0 * M * d * V_t / gemm_s / 1e12, 1) if gemm_s > 0 else None,
         "lm_head_frac_mfma_peak": round(2.0 * M * d * V_t / gemm_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4) if gemm_s > 0 else None,
-        "target_stats_gbs": round(stats_bytes / (stage_us["target_stats"] * 1e-6) / 1e9, 1) if stage_us["target_stats"] > 0 else None,
-        "target_stats_frac_hbm_peak": round(stats_bytes / (stage_us["target_stats"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if stage_us["target_stats"] > 0 else None,
+        "softmax_stats_gbs": round(stats_bytes / (stage_us["softmax_stats"] * 1e-6) / 1e9, 1) if stage_us["softmax_stats"] > 0 else None,
+        "softmax_stats_frac_hbm_peak": round(stats_bytes / (stage_us["softmax_stats"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if stage_us["softmax_stats"] > 0 else None,
         "rows_per_s": round(M * args.steps / elapsed, 1),
-        "step_hbm_bytes": gemm_bytes + stats_bytes + esz * K * V_d + case.B * (4 * V_t + esz * V_d + 4 * V_t),
+        "step_hbm_bytes": gemm_bytes + stats_bytes + case.B * (4 * V_t + esz * V_d + 4 * V_t),
     }
     extra["step_frac_hbm_roofline"] = round(extra["step_hbm_bytes"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
 

@@ -19,9 +19,7 @@
  *     ot_last_error() returns a thread-local, NUL-terminated description of the last failure on this thread.
  *   - Pointers are marked HOST or DEVICE.  The library never frees or reallocates caller memory.
  *   - Device work is enqueued on the stream given at init and is asynchronous: the caller synchronises that
- *     stream before reading outputs.  (The draft-side kernels run on a second, internal stream that is forked
- *     from and joined back into the caller's stream inside every step.)  One context must not be used from two
- *     threads at once.
+ *     stream before reading outputs.  One context must not be used from two threads at once.
  *   - Uniform random numbers are Philox4x32-10 (Salmon et al., SC'11) with key = (seed low, seed high) and
  *     counter = (mapped position j, step, seq_id low, seq_id high).  Output word 0 gives the acceptance
  *     uniform of position j, word 1 the uniform of the final-token draw at row j; a uniform is the word's top
@@ -158,18 +156,15 @@ typedef struct ot_workspace_view {
 } ot_workspace_view;
 int ot_verify_workspace(ot_ctx* ctx, ot_workspace_view* view);
 
-/* Kernel timing.  While enabled, every step records HIP events around its kernels on the streams they run on
- * (the two draft-side kernels run on an internal side stream, concurrently with the LM head).
+/* Kernel timing.  While enabled, every step records HIP events between its kernels on the context's stream.
  * ot_verify_profile_read synchronises the stream, adds the elapsed milliseconds of the steps run since the
  * last read into ms[0 .. OT_N_STAGES) (overwriting it), stores the number of steps in *n_steps and resets.    */
-#define OT_STAGE_DRAFT_STATS   0   /* softmax statistics of the draft rows (side stream)                      */
-#define OT_STAGE_MAP           1   /* translation scan and n-gram cache probes, Eq. 1 (side stream)           */
-#define OT_STAGE_LM_HEAD       2   /* z = h . W                                                               */
-#define OT_STAGE_TARGET_STATS  3   /* softmax statistics of the target rows                                   */
-#define OT_STAGE_ACCEPT        4   /* acceptance ratios, Philox uniforms, first rejection                     */
-#define OT_STAGE_RESID_SUMS    5   /* partial masses of max(0, p - q') (Eq. 2) at the final row               */
-#define OT_STAGE_RESID_PICK    6   /* inverse-CDF pick of the final token                                     */
-#define OT_N_STAGES            7
+#define OT_STAGE_LM_HEAD          0   /* z = h . W                                                            */
+#define OT_STAGE_SOFTMAX_STATS    1   /* softmax statistics of the target rows and of the draft rows          */
+#define OT_STAGE_TRANSLATE_ACCEPT 2   /* translation scan + n-gram probes (Eq. 1), acceptance ratios, Philox  */
+#define OT_STAGE_RESID_SUMS       3   /* partial masses of max(0, p - q') (Eq. 2) at the final row            */
+#define OT_STAGE_RESID_PICK       4   /* inverse-CDF pick of the final token                                  */
+#define OT_N_STAGES               5
 int ot_verify_profile(ot_ctx* ctx, int32_t enable);
 int ot_verify_profile_read(ot_ctx* ctx, float* ms, int32_t* n_steps);
 

@@ -20,8 +20,8 @@ OT_ERR_NGRAM, OT_ERR_CTX_MISMATCH, OT_ERR_HIP, OT_ERR_NOMEM = -5, -6, -7, -8
 OT_BF16, OT_F32 = 0, 1
 OT_FLAG_UNMAPPABLE, OT_FLAG_RESID_ZERO, OT_FLAG_BAD_ID = 1, 2, 4
 OT_MAX_NGRAM_LEN, OT_MAX_K = 8, 63
-OT_N_STAGES = 7
-STAGE_NAMES = ("draft_stats", "map", "lm_head", "target_stats", "accept", "resid_sums", "resid_pick")
+OT_N_STAGES = 5
+STAGE_NAMES = ("lm_head", "softmax_stats", "translate_accept", "resid_sums", "resid_pick")
 
 EXPORTS = (
     "ot_verify_init", "ot_verify_destroy", "ot_ngram_cache_build", "ot_ngram_cache_destroy", "ot_verify_step",

@@ -28,7 +28,7 @@ int fail_hip(hipError_t e, const char* what) {
 }
 
 constexpr int kProfileCapacity = 1024;   // steps whose events can be pending between two profile reads
-constexpr int kEventsPerStep = 9;        // side: 0 draft stats 1 map 2 | main: 3 LM head 4 stats 5 accept 6 sums 7 pick 8
+constexpr int kEventsPerStep = OT_N_STAGES + 1;
 
 }  // namespace
 
@@ -46,12 +46,8 @@ struct ot_ctx {
   float *tpart_max = nullptr, *dpart_max = nullptr, *row_max = nullptr, *drow_max = nullptr;
   double *tpart_sum = nullptr, *dpart_sum = nullptr, *row_sum = nullptr, *drow_sum = nullptr;
   int32_t *tpart_arg = nullptr, *dpart_arg = nullptr, *row_arg = nullptr, *drow_arg = nullptr;
-  double *logq_tok = nullptr, *logq_map = nullptr, *tile_r = nullptr, *tile_p = nullptr;
-  int32_t* s_end = nullptr;
+  double *tile_r = nullptr, *tile_p = nullptr;
   FinalInfo* fin = nullptr;
-  // the draft-side kernels run on a side stream, concurrently with the LM head
-  hipStream_t side = nullptr;
-  hipEvent_t fork = nullptr, join = nullptr;
   // profiling
   bool profiling = false;
   std::vector<hipEvent_t> events;   // kEventsPerStep per pending step
@@ -82,9 +78,6 @@ bool dev_alloc(ot_ctx* c, T** p, size_t count) {
 void free_ctx(ot_ctx* c) {
   for (void* p : c->allocs) (void)hipFree(p);
   for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
-  if (c->fork) (void)hipEventDestroy(c->fork);
-  if (c->join) (void)hipEventDestroy(c->join);
-  if (c->side) (void)hipStreamDestroy(c->side);
   delete c;
 }
 
@@ -150,15 +143,11 @@ int ot_verify_init(const ot_verify_config* cfg, ot_ctx** out) {
   ok = ok && dev_alloc(c, &c->dpart_max, KQ * c->nchd) && dev_alloc(c, &c->dpart_sum, KQ * c->nchd) && dev_alloc(c, &c->dpart_arg, KQ * c->nchd);
   ok = ok && dev_alloc(c, &c->row_max, R) && dev_alloc(c, &c->row_sum, R) && dev_alloc(c, &c->row_arg, R);
   ok = ok && dev_alloc(c, &c->drow_max, KQ) && dev_alloc(c, &c->drow_sum, KQ) && dev_alloc(c, &c->drow_arg, KQ);
-  ok = ok && dev_alloc(c, &c->logq_tok, KQ) && dev_alloc(c, &c->logq_map, R);
-  ok = ok && dev_alloc(c, &c->s_end, Bm) && dev_alloc(c, &c->fin, Bm);
+  ok = ok && dev_alloc(c, &c->fin, Bm);
   ok = ok && dev_alloc(c, &c->tile_r, Bm * c->ntiles) && dev_alloc(c, &c->tile_p, Bm * c->ntiles);
   if (!ok) { free_ctx(c); return fail(OT_ERR_NOMEM, "ot_verify_init: device allocation failed"); }
 
-  e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
-  if (e == hipSuccess) e = hipEventCreateWithFlags(&c->fork, hipEventDisableTiming);
-  if (e == hipSuccess) e = hipEventCreateWithFlags(&c->join, hipEventDisableTiming);
-  if (e == hipSuccess && c->zeros) e = hipMemsetAsync(c->zeros, 0, 64, c->stream);
+  if (c->zeros) e = hipMemsetAsync(c->zeros, 0, 64, c->stream);
   if (e == hipSuccess) e = hipMemcpyAsync(c->dmap, cfg->direct_map, sizeof(int32_t) * c->V_d, hipMemcpyHostToDevice, c->stream);
   if (e == hipSuccess) e = hipMemcpyAsync(c->tmap, tmap_h.data(), sizeof(int32_t) * c->V_t, hipMemcpyHostToDevice, c->stream);
   if (e == hipSuccess) {
@@ -176,7 +165,6 @@ int ot_verify_init(const ot_verify_config* cfg, ot_ctx** out) {
 void ot_verify_destroy(ot_ctx* ctx) {
   if (!ctx) return;
   (void)hipStreamSynchronize(ctx->stream);
-  if (ctx->side) (void)hipStreamSynchronize(ctx->side);
   free_ctx(ctx);
 }
 
@@ -282,11 +270,11 @@ static int step_impl(ot_ctx* ctx, const ot_ngram_cache* cache, const ot_step_in*
   a.dpart_max = ctx->dpart_max; a.dpart_sum = ctx->dpart_sum; a.dpart_arg = ctx->dpart_arg;
   a.row_max = ctx->row_max; a.row_sum = ctx->row_sum; a.row_arg = ctx->row_arg;
   a.drow_max = ctx->drow_max; a.drow_sum = ctx->drow_sum; a.drow_arg = ctx->drow_arg;
-  a.logq_tok = ctx->logq_tok; a.logq_map = ctx->logq_map; a.s_end = ctx->s_end; a.fin = ctx->fin;
+  a.fin = ctx->fin;
   a.tile_r = ctx->tile_r; a.tile_p = ctx->tile_p;
   a.out = *o;
 
-  hipStream_t st = ctx->stream, side = ctx->side;
+  hipStream_t st = ctx->stream;
   hipEvent_t* ev = nullptr;
   if (ctx->profiling && ctx->pending < kProfileCapacity) {
     const size_t need = (size_t)(ctx->pending + 1) * kEventsPerStep;
@@ -299,17 +287,8 @@ static int step_impl(ot_ctx* ctx, const ot_ngram_cache* cache, const ot_step_in*
     ev = &ctx->events[(size_t)ctx->pending * kEventsPerStep];
   }
   hipError_t e = hipSuccess;
-#define OT_MARK(i, s) do { if (ev && e == hipSuccess) e = hipEventRecord(ev[i], s); } while (0)
-  // fork: the draft-side kernels (statistics of q, translation) do not depend on the LM head
-  e = hipEventRecord(ctx->fork, st);
-  if (e == hipSuccess) e = hipStreamWaitEvent(side, ctx->fork, 0);
-  OT_MARK(0, side);
-  if (e == hipSuccess) e = launch_draft_stats(a, side);
-  OT_MARK(1, side);
-  if (e == hipSuccess) e = launch_map(a, side);
-  OT_MARK(2, side);
-  if (e == hipSuccess) e = hipEventRecord(ctx->join, side);
-  OT_MARK(3, st);
+#define OT_MARK(i) do { if (ev && e == hipSuccess) e = hipEventRecord(ev[i], st); } while (0)
+  OT_MARK(0);
   if (e == hipSuccess && !from_logits) {
     if (ctx->dtype == OT_BF16)
       e = launch_lmhead_bf16(static_cast<const uint16_t*>(in->hidden), M, ctx->d, ctx->Wp, ctx->Kp, ctx->Vp, ctx->Z,
@@ -317,17 +296,15 @@ static int step_impl(ot_ctx* ctx, const ot_ngram_cache* cache, const ot_step_in*
     else
       e = launch_lmhead_f32(static_cast<const float*>(in->hidden), M, ctx->d, ctx->Wf, ctx->Z, ctx->V_t, a.ldz, st);
   }
-  OT_MARK(4, st);
-  if (e == hipSuccess) e = launch_target_stats(a, st);
-  OT_MARK(5, st);
-  // join: acceptance needs the translated proposal
-  if (e == hipSuccess) e = hipStreamWaitEvent(st, ctx->join, 0);
-  if (e == hipSuccess) e = launch_accept(a, st);
-  OT_MARK(6, st);
+  OT_MARK(1);
+  if (e == hipSuccess) e = launch_softmax_stats(a, st);
+  OT_MARK(2);
+  if (e == hipSuccess) e = launch_translate_accept(a, st);
+  OT_MARK(3);
   if (e == hipSuccess) e = launch_resid_sums(a, st);
-  OT_MARK(7, st);
+  OT_MARK(4);
   if (e == hipSuccess) e = launch_resid_pick(a, st);
-  OT_MARK(8, st);
+  OT_MARK(5);
 #undef OT_MARK
   if (e != hipSuccess) return fail_hip(e, "ot_verify_step: launch");
   if (ev) ctx->pending += 1;
@@ -362,12 +339,11 @@ int ot_verify_profile_read(ot_ctx* ctx, float* ms, int32_t* n_steps) {
   hipError_t e = hipStreamSynchronize(ctx->stream);
   if (e != hipSuccess) return fail_hip(e, "ot_verify_profile_read: synchronize");
   for (int s = 0; s < OT_N_STAGES; ++s) ms[s] = 0.f;
-  static const int first[OT_N_STAGES] = {0, 1, 3, 4, 5, 6, 7};     // stage s spans events first[s] .. first[s] + 1
   for (int p = 0; p < ctx->pending; ++p) {
     hipEvent_t* ev = &ctx->events[(size_t)p * kEventsPerStep];
     for (int s = 0; s < OT_N_STAGES; ++s) {
       float t = 0.f;
-      e = hipEventElapsedTime(&t, ev[first[s]], ev[first[s] + 1]);
+      e = hipEventElapsedTime(&t, ev[s], ev[s + 1]);
       if (e != hipSuccess) return fail_hip(e, "hipEventElapsedTime");
       ms[s] += t;
     }

@@ -39,7 +39,7 @@ __host__ __device__ inline uint32_t hash_ngram(const int32_t* ids, int len) {
 }
 
 // ------------------------------------------------------------------------------------------------ per-step view
-// What the final-token kernels need to know about sequence b; written by the acceptance kernel.
+// What the final-token kernels need to know about sequence b; written by the translate-and-accept kernel.
 struct FinalInfo {
   int32_t mode;          // 0: nothing to draw (greedy, or bad id), 2: draw from p (free token), 3: draw from the residual
   int32_t row;           // global row of the final token (row_off[b] + n_b)
@@ -80,9 +80,6 @@ struct StepArgs {
   float* dpart_max; double* dpart_sum; int32_t* dpart_arg;   // [K, nchd]
   float* row_max; double* row_sum; int32_t* row_arg;         // [M]
   float* drow_max; double* drow_sum; int32_t* drow_arg;      // [K]
-  double* logq_tok;      // [K] log q_i(d_i)
-  double* logq_map;      // [M] log q'(t_j)
-  int32_t* s_end;        // [B] draft position where the scan stopped
   FinalInfo* fin;        // [B]
   int32_t ntiles;        // residual tiles per row
   double* tile_r; double* tile_p;                            // [B, ntiles]
@@ -97,10 +94,8 @@ hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* W
                               int64_t ldz, const uint16_t* zeros, hipStream_t stream);
 hipError_t launch_lmhead_f32(const float* H, int M, int d, const float* W, float* Z, int V_t, int64_t ldz,
                              hipStream_t stream);
-hipError_t launch_draft_stats(const StepArgs& a, hipStream_t stream);
-hipError_t launch_map(const StepArgs& a, hipStream_t stream);
-hipError_t launch_target_stats(const StepArgs& a, hipStream_t stream);
-hipError_t launch_accept(const StepArgs& a, hipStream_t stream);
+hipError_t launch_softmax_stats(const StepArgs& a, hipStream_t stream);
+hipError_t launch_translate_accept(const StepArgs& a, hipStream_t stream);
 hipError_t launch_resid_sums(const StepArgs& a, hipStream_t stream);
 hipError_t launch_resid_pick(const StepArgs& a, hipStream_t stream);
 
