@@ -63,7 +63,7 @@ typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 // s_waitcnt immediate (gfx9 encoding) that waits until at most N vector-memory loads are outstanding and nothing else
 constexpr int vmcnt_imm(int n) { return (n & 0xF) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
 
-template <int MT, int PF, int WPG, int KC>
+template <int MT, int PF, int WPG, int KC, int NW>
 __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16_t* __restrict__ H, int M, int d,
                                                                     const uint4* __restrict__ Wp, int nks,
                                                                     int n_wtiles, float* __restrict__ Z, int V_t,
@@ -73,27 +73,30 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
   constexpr int kCPR = KC / 8;                     // 16-byte chunks per slice row
   constexpr int kSliceChunks = MT * 16 * kCPR;
   constexpr int kDma = (kSliceChunks + WPG * 64 - 1) / (WPG * 64);
-  static_assert(kKSteps % PF == 0 && kGemmKPad % KC == 0 && kCPR >= 16 && kKSteps * 4 < 64, "slice geometry");
+  constexpr int kPatchRow = NW * 16 + 4;           // floats per padded row of the epilogue patch
+  static_assert(kKSteps % PF == 0 && kGemmKPad % KC == 0 && kCPR >= 16 && kKSteps * NW < 64, "slice geometry");
+  static_assert(NW == 1 || NW == 2 || NW == 4, "a wavefront owns 16, 32 or 64 columns");
   __shared__ __attribute__((aligned(16))) uint16_t sA[MT * 16 * KC];
   __shared__ __attribute__((aligned(16))) uint16_t sB[MT * 16 * KC];
-  __shared__ __attribute__((aligned(16))) float sPatch[WPG][16 * 68];   // epilogue: one 16 x 64 tile per wavefront
+  __shared__ __attribute__((aligned(16))) float sPatch[WPG][16 * kPatchRow];   // epilogue: one 16-row tile per wavefront
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   // Workgroup id -> (column tile, M-block).  Consecutive ids go round-robin to the 8 XCDs, each with its own L2; the
   // M-blocks of one column tile get ids that land on the same XCD back to back, so that when M needs several
   // blocks their weight streams coincide in that XCD's L2 and HBM is still read once.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int col_tile = (slot / m_blocks) * 8 + xcd, m_block = slot % m_blocks;
-  const int wt = col_tile * WPG + wave;
-  if (col_tile * WPG >= n_wtiles) return;            // padding of the id space (whole workgroup)
-  const bool active = wt < n_wtiles;
+  const int t16 = (col_tile * WPG + wave) * NW;       // first 16-column tile of this wavefront
+  if (col_tile * WPG * NW >= n_wtiles * 4) return;    // padding of the id space (whole workgroup)
+  const bool active = t16 < n_wtiles * 4;
   const int row0 = m_block * (MT * 16);
-  const uint4* wp = Wp + ((int64_t)(active ? wt : 0) * nks) * 256 + lane;
+  // fragment (16-column tile t, step ks) sits at 16-byte unit (((t/4) * nks + ks) * 4 + t%4) * 64 + lane
+  const uint4* wp = Wp + ((int64_t)((active ? t16 : 0) / 4) * nks * 4 + (t16 % 4)) * 64 + lane;
 
-  f32x4 acc[MT][4];
+  f32x4 acc[MT][NW];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int nw = 0; nw < 4; ++nw) acc[mt][nw] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int nw = 0; nw < NW; ++nw) acc[mt][nw] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   // request slice kc (in 32-column steps) into buffer s: chunk q of the buffer holds logical chunk (q%kCPR)^(row&15)
   auto request = [&](int kc, uint16_t* s) {
@@ -113,11 +116,11 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
   };
 
   request(0, sA);
-  uint4 bq[PF][4];
+  uint4 bq[PF][NW];
 #pragma unroll
   for (int s = 0; s < PF; ++s)
 #pragma unroll
-    for (int nw = 0; nw < 4; ++nw) bq[s][nw] = (active && s < nks) ? wp[(s * 4 + nw) * 64] : make_uint4(0, 0, 0, 0);
+    for (int nw = 0; nw < NW; ++nw) bq[s][nw] = (active && s < nks) ? wp[(s * 4 + nw) * 64] : make_uint4(0, 0, 0, 0);
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
   __syncthreads();
 
@@ -133,7 +136,7 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
         const uint4 hv = *reinterpret_cast<const uint4*>(&hs[(mt * 16 + a_row) * KC + pc * 8]);
         const bf16x8 hf = __builtin_bit_cast(bf16x8, hv);
 #pragma unroll
-        for (int nw = 0; nw < 4; ++nw) {
+        for (int nw = 0; nw < NW; ++nw) {
           acc[mt][nw] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bq[ks % PF][nw]), hf,
                                                                 acc[mt][nw], 0, 0, 0);
         }
@@ -141,16 +144,16 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
       // the slot is free again: refill it with the fragments PF steps ahead
       if (kk + PF < nks) {
 #pragma unroll
-        for (int nw = 0; nw < 4; ++nw) bq[ks % PF][nw] = wp[((int64_t)(kk + PF) * 4 + nw) * 64];
+        for (int nw = 0; nw < NW; ++nw) bq[ks % PF][nw] = wp[((int64_t)(kk + PF) * 4 + nw) * 64];
       }
       __builtin_amdgcn_sched_barrier(0);   // keep the next step's LDS reads from being hoisted (register budget)
     }
   };
-  // Loads complete in issue order, so once at most kKSteps*4 loads (the weight fragments requested during the slice)
+  // Loads complete in issue order, so once at most kKSteps*NW loads (the weight fragments requested during the slice)
   // are outstanding, this wavefront's part of the next hidden slice has landed in LDS.
   auto hand_over = [&](int kc) {
     __builtin_amdgcn_sched_barrier(0);
-    if (active && kc + kKSteps - 1 + PF < nks) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kKSteps * 4));
+    if (active && kc + kKSteps - 1 + PF < nks) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kKSteps * NW));
     else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     __syncthreads();
   };
@@ -168,22 +171,25 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
     hand_over(kc + kKSteps);
   }
   if (!active) return;
-  // Epilogue.  After the MFMAs a lane holds Z[row0 + mt*16 + lane%16][wt*64 + nw*16 + 4*(lane/16) + 0..3]: 64-byte
-  // pieces of 16 rows per store.  Each 16 x 64 tile is turned through a wave-private LDS patch (rows padded to 68
-  // floats) so that a store instruction writes 4 rows x 256 contiguous bytes, and the logits are written with
+  // Epilogue.  After the MFMAs a lane holds Z[row0 + mt*16 + lane%16][(t16 + nw)*16 + 4*(lane/16) + 0..3]: 64-byte
+  // pieces of 16 rows per store.  Each 16-row tile is turned through a wave-private LDS patch (padded rows) so that a
+  // store instruction writes whole rows of the wavefront's columns contiguously, and the logits are written with
   // nontemporal stores: they are not re-read by this kernel and should not evict the weight stream.
   float* patch = sPatch[wave];
+  constexpr int kVecPerRow = NW * 4;                   // float4 per patch row
+  constexpr int kIters = 16 * kVecPerRow / 64;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
-    for (int nw = 0; nw < 4; ++nw)
-      *reinterpret_cast<f32x4*>(&patch[(lane & 15) * 68 + nw * 16 + 4 * (lane >> 4)]) = acc[mt][nw];
+    for (int nw = 0; nw < NW; ++nw)
+      *reinterpret_cast<f32x4*>(&patch[(lane & 15) * kPatchRow + nw * 16 + 4 * (lane >> 4)]) = acc[mt][nw];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int r = (lane >> 4) + 4 * i;
-      const f32x4 v = *reinterpret_cast<const f32x4*>(&patch[r * 68 + 4 * (lane & 15)]);
+    for (int i = 0; i < kIters; ++i) {
+      const int idx = i * 64 + lane;
+      const int r = idx / kVecPerRow, c4 = idx % kVecPerRow;
+      const f32x4 v = *reinterpret_cast<const f32x4*>(&patch[r * kPatchRow + 4 * c4]);
       const int m = row0 + mt * 16 + r;
-      const int n = wt * 64 + 4 * (lane & 15);
+      const int n = t16 * 16 + 4 * c4;
       if (m < M) {
         float* dst = Z + (int64_t)m * ldz + n;
         if (vec_store && n + 3 < V_t) {
@@ -284,14 +290,14 @@ __global__ __launch_bounds__(256) void lmhead_f32_kernel(const float* __restrict
   Z[(int64_t)m * ldz + n] = acc;
 }
 
-template <int MT, int PF, int WPG, int KC>
+template <int MT, int PF, int WPG, int KC, int NW>
 hipError_t launch_wide(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
                        int64_t ldz, const uint16_t* zeros, hipStream_t stream) {
   const int nks = Kp / 32, n_wtiles = Vp / kGemmColsPerWave;
   const int m_blocks = ceil_div(M, MT * 16);
-  dim3 grid(ceil_div(ceil_div(n_wtiles, WPG), 8) * 8 * m_blocks), block(WPG * 64);
+  dim3 grid(ceil_div(ceil_div(n_wtiles * 4, WPG * NW), 8) * 8 * m_blocks), block(WPG * 64);
   const int vec_store = (ldz % 4 == 0) && (reinterpret_cast<uintptr_t>(Z) % 16 == 0);
-  hipLaunchKernelGGL((lmhead_bf16_wide_kernel<MT, PF, WPG, KC>), grid, block, 0, stream, H, M, d,
+  hipLaunchKernelGGL((lmhead_bf16_wide_kernel<MT, PF, WPG, KC, NW>), grid, block, 0, stream, H, M, d,
                      reinterpret_cast<const uint4*>(Wp), nks, n_wtiles, Z, V_t, ldz, vec_store, zeros, m_blocks);
   return hipGetLastError();
 }
@@ -316,10 +322,10 @@ hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* W
                        reinterpret_cast<const uint4*>(Wp), nks, Z, V_t, ldz);
     return hipGetLastError();
   }
-  if (tiles <= 2) return launch_wide<2, 4, 4, 128>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
-  if (tiles <= 4) return launch_wide<4, 4, 4, 128>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
-  if (tiles <= 6) return launch_wide<6, 4, 4, 128>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
-  return launch_wide<9, 4, 4, 128>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
+  if (tiles <= 2) return launch_wide<2, 4, 4, 128, 4>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
+  if (tiles <= 4) return launch_wide<4, 4, 4, 128, 4>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
+  if (tiles <= 6) return launch_wide<6, 4, 4, 128, 4>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
+  return launch_wide<9, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
 }
 
 hipError_t launch_lmhead_f32(const float* H, int M, int d, const float* W, float* Z, int V_t, int64_t ldz,
