@@ -223,6 +223,7 @@ def verify_step(*, row_off, draft_ids, draft_logits, direct_map, V_t: int, cache
         "row_max": Z.max(axis=1) if M else np.zeros(0), "row_argmax": Z.argmax(axis=1) if M else np.zeros(0, np.int64),
         "row_sumexp": np.zeros(M), "final_row": np.full(B, -1, np.int32),
         "cdf_neighbors": np.full((B, 2), -1, np.int64),
+        "used_keys": [],          # draft-id tuples of the cache entries the translation used, in batch order
     }
     if return_logits:
         out["logits"] = Z
@@ -257,6 +258,7 @@ def verify_step(*, row_off, draft_ids, draft_logits, direct_map, V_t: int, cache
             out["span_start"][r0 + j], out["span_len"][r0 + j] = spans[j]
             out["q_tok"][r0 + j] = qprime[j]
         out["hits_proposed"][b] = sum(1 for sp in spans if sp[1] > 1)
+        out["used_keys"] += [tuple(int(v) for v in d[sp[0]:sp[0] + sp[1]]) for sp in spans if sp[1] > 1]
 
         # ---- rejection sampling, Algorithm 1: accept t_j with probability min(1, p(t_j)/q'(t_j))
         accepted = np.zeros(m, dtype=bool)
