@@ -84,15 +84,40 @@ typedef struct ot_verify_config {
 int  ot_verify_init(const ot_verify_config* cfg, ot_ctx** out);
 void ot_verify_destroy(ot_ctx* ctx);          /* synchronises the stream, frees everything; NULL is a no-op   */
 
-/* ---- ot_ngram_cache_build ------------------------------------------------------------------------------ */
-/* The n-gram cache C = {(t_i, [d_j]_{j=1:n})} (Section "Cross-vocabulary N-gram Cache") in CSR form on the
- * HOST: entry e maps draft ids key_ids[key_off[e] .. key_off[e+1]) (2 <= length <= cfg.max_ngram_len, ids in
- * [0, V_d)) to target_ids[e] in [0, V_t).  Of entries with equal keys the last one wins.  n_entries may be 0.
- * Builds an open-addressing hash table on the host and copies it to the device (synchronous).  The arrays
- * are not referenced after return.  The cache may be used only with the context it was built for and must
- * be destroyed before that context.                                                                          */
+/* ---- the n-gram cache ---------------------------------------------------------------------------------- */
+/* The cache C = {(t_i, [d_j]_{j=1:n})} (Section "Cross-vocabulary N-gram Cache") lives on the device as an
+ * open-addressing hash table that the translation step probes.  Entries are given in CSR form on the HOST: entry e
+ * maps draft ids key_ids[key_off[e] .. key_off[e+1]) (2 <= length <= cfg.max_ngram_len, ids in [0, V_d)) to
+ * target_ids[e] in [0, V_t); the arrays are not referenced after a call returns.  Of pairs with equal keys the last
+ * one wins.  A cache may be used only with the context it was made for and must be destroyed before it.  The calls
+ * below synchronise the context's stream: cache maintenance happens between steps.
+ *
+ * Every verification step that is handed a cache advances the cache's logical clock by one and, for each entry
+ * the translation scan uses (the entry becomes a mapped token of a proposal, accepted or not), adds one to the
+ * entry's use count and stamps it with the clock.  Every insert call advances the clock by one and stamps the
+ * entries it adds or overwrites.                                                                              */
+#define OT_EVICT_NONE 0   /* an insert call whose new keys do not fit fails as a whole (OT_ERR_SHAPE)             */
+#define OT_EVICT_LRU  1   /* evict the entry not used for the longest time        (Appendix "N-gram Cache        */
+#define OT_EVICT_LFU  2   /* evict the entry with the fewest uses                  Scalability")                 */
+
+/* Bulk build: a cache of capacity n_entries without eviction holding the given entries.  n_entries may be 0.  */
 int  ot_ngram_cache_build(ot_ctx* ctx, int32_t n_entries, const int32_t* key_off, const int32_t* key_ids,
                           const int32_t* target_ids, ot_ngram_cache** out);
+/* An empty cache for at most `capacity` entries (0 .. 2^26) with the given eviction policy.                    */
+int  ot_ngram_cache_create(ot_ctx* ctx, int32_t capacity, int32_t policy, ot_ngram_cache** out);
+/* Online update (Algorithm 1, "Add to n-gram cache if there exists unseen n-gram instance"): adds the pairs in
+ * order.  A known key gets the new target and a fresh time stamp and keeps its use count.  A new key that finds
+ * the cache full first evicts one entry: LRU the smallest (last use, insertion number), LFU the smallest (uses,
+ * last use, insertion number).  *n_evicted (may be NULL) receives the number of evictions.                     */
+int  ot_ngram_cache_insert(ot_ngram_cache* cache, int32_t n_entries, const int32_t* key_off, const int32_t* key_ids,
+                           const int32_t* target_ids, int32_t* n_evicted);
+/* Number of entries and (if n_key_ids is not NULL) total number of key ids, i.e. the sizes ot_ngram_cache_export
+ * needs.                                                                                                       */
+int  ot_ngram_cache_size(const ot_ngram_cache* cache, int32_t* n_entries, int32_t* n_key_ids);
+/* Copies the entries out in insertion order: HOST key_off [n+1], key_ids, target_ids [n], and, if not NULL, the
+ * use counts and last-use clocks [n].  OT_ERR_SHAPE if max_entries / max_key_ids are too small.                */
+int  ot_ngram_cache_export(ot_ngram_cache* cache, int32_t max_entries, int32_t max_key_ids, int32_t* key_off,
+                           int32_t* key_ids, int32_t* target_ids, int64_t* uses, int64_t* last_used);
 void ot_ngram_cache_destroy(ot_ngram_cache* cache);
 
 /* ---- ot_verify_step ------------------------------------------------------------------------------------ */
@@ -134,11 +159,11 @@ typedef struct ot_step_out {
 
 /* Enqueues one verification step.  `cache` may be NULL (direct map only).  Returns OT_ERR_SHAPE if B or any
  * k_b exceeds the capacity or row_off_host is not increasing by at least 1 per sequence.  B == 0 is a no-op. */
-int ot_verify_step(ot_ctx* ctx, const ot_ngram_cache* cache, const ot_step_in* in, ot_step_out* out);
+int ot_verify_step(ot_ctx* ctx, ot_ngram_cache* cache_or_null, const ot_step_in* in, ot_step_out* out);
 
 /* Same, but the LM-head projection is skipped and `target_logits` (DEVICE [M, V_t] row-major fp32, the z_j of
  * Algorithm 1's target pass) is used instead; in->hidden is ignored.                                          */
-int ot_verify_step_from_logits(ot_ctx* ctx, const ot_ngram_cache* cache, const ot_step_in* in,
+int ot_verify_step_from_logits(ot_ctx* ctx, ot_ngram_cache* cache_or_null, const ot_step_in* in,
                                const float* target_logits, ot_step_out* out);
 
 /* ---- diagnostics ---------------------------------------------------------------------------------------- */

@@ -62,6 +62,8 @@ class NgramCache:
     def insert(self, items: Iterable[Tuple[Tuple[int, ...], int]]) -> int:
         """Adds (key, target) pairs in order; returns the number of evicted entries."""
         items = [(tuple(int(x) for x in k), int(t)) for k, t in items]
+        if not items:
+            return 0
         if self.policy == "none":
             new_keys = {k for k, _ in items if k not in self.entries}
             if len(self.entries) + len(new_keys) > self.capacity:

@@ -23,8 +23,11 @@ OT_MAX_NGRAM_LEN, OT_MAX_K = 8, 63
 OT_N_STAGES = 5
 STAGE_NAMES = ("lm_head", "softmax_stats", "translate_accept", "resid_sums", "resid_pick")
 
+OT_EVICT_NONE, OT_EVICT_LRU, OT_EVICT_LFU = 0, 1, 2
+
 EXPORTS = (
-    "ot_verify_init", "ot_verify_destroy", "ot_ngram_cache_build", "ot_ngram_cache_destroy", "ot_verify_step",
+    "ot_verify_init", "ot_verify_destroy", "ot_ngram_cache_build", "ot_ngram_cache_create", "ot_ngram_cache_insert",
+    "ot_ngram_cache_size", "ot_ngram_cache_export", "ot_ngram_cache_destroy", "ot_verify_step",
     "ot_verify_step_from_logits", "ot_verify_workspace", "ot_verify_profile", "ot_verify_profile_read",
     "ot_last_error", "ot_version",
 )
@@ -91,6 +94,15 @@ def load_library() -> C.CDLL:
     lib.ot_ngram_cache_build.restype = C.c_int
     lib.ot_ngram_cache_destroy.argtypes = [C.c_void_p]
     lib.ot_ngram_cache_destroy.restype = None
+    lib.ot_ngram_cache_create.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
+    lib.ot_ngram_cache_create.restype = C.c_int
+    lib.ot_ngram_cache_insert.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_int32)]
+    lib.ot_ngram_cache_insert.restype = C.c_int
+    lib.ot_ngram_cache_size.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    lib.ot_ngram_cache_size.restype = C.c_int
+    lib.ot_ngram_cache_export.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_void_p, C.c_void_p]
+    lib.ot_ngram_cache_export.restype = C.c_int
     lib.ot_verify_step.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(ot_step_in), C.POINTER(ot_step_out)]
     lib.ot_verify_step.restype = C.c_int
     lib.ot_verify_step_from_logits.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(ot_step_in), C.c_void_p, C.POINTER(ot_step_out)]
@@ -162,6 +174,42 @@ def ot_ngram_cache_build(ctx, key_off, key_ids, target_ids):
 
 def ot_ngram_cache_destroy(cache):
     load_library().ot_ngram_cache_destroy(cache)
+
+
+def ot_ngram_cache_create(ctx, capacity: int, policy: int):
+    out = C.c_void_p()
+    _check(load_library().ot_ngram_cache_create(ctx, int(capacity), int(policy), C.byref(out)))
+    return out
+
+
+def ot_ngram_cache_insert(cache, key_off, key_ids, target_ids) -> int:
+    """Host int32 CSR arrays of the pairs to add; returns the number of evicted entries."""
+    ko = np.ascontiguousarray(key_off, dtype=np.int32)
+    ki = np.ascontiguousarray(key_ids, dtype=np.int32)
+    ti = np.ascontiguousarray(target_ids, dtype=np.int32)
+    ev = C.c_int32()
+    _check(load_library().ot_ngram_cache_insert(cache, int(ti.size), _ptr(ko), _ptr(ki), _ptr(ti), C.byref(ev)))
+    return int(ev.value)
+
+
+def ot_ngram_cache_size(cache):
+    """(number of entries, total number of key ids)."""
+    n, ids = C.c_int32(), C.c_int32()
+    _check(load_library().ot_ngram_cache_size(cache, C.byref(n), C.byref(ids)))
+    return int(n.value), int(ids.value)
+
+
+def ot_ngram_cache_export(cache) -> dict:
+    """Entries in insertion order with their use counts and last-use clocks (numpy arrays)."""
+    n, ids = ot_ngram_cache_size(cache)
+    out = {"key_off": np.zeros(n + 1, np.int32), "key_ids": np.zeros(max(ids, 1), np.int32),
+           "target_ids": np.zeros(max(n, 1), np.int32), "uses": np.zeros(max(n, 1), np.int64),
+           "last_used": np.zeros(max(n, 1), np.int64)}
+    _check(load_library().ot_ngram_cache_export(cache, n, ids, _ptr(out["key_off"]), _ptr(out["key_ids"]),
+                                                _ptr(out["target_ids"]), _ptr(out["uses"]), _ptr(out["last_used"])))
+    out["key_ids"], out["target_ids"] = out["key_ids"][:ids], out["target_ids"][:n]
+    out["uses"], out["last_used"] = out["uses"][:n], out["last_used"][:n]
+    return out
 
 
 def make_step_in(*, B, step, row_off, row_off_host, hidden, draft_logits, draft_ids, temperature,

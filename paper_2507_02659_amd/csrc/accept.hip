@@ -24,6 +24,7 @@ namespace otv {
 namespace {
 
 // Probe of one key held in registers (fully unrolled so that `ids` never has to live in scratch memory).
+// Returns the slot index of the entry, or -1.
 __device__ inline int cache_lookup(const CacheTable& C, const int32_t (&ids)[OT_MAX_NGRAM_LEN], int L) {
   uint32_t h = 0x9E3779B9u ^ (uint32_t)L;                  // same mixing as hash_ngram()
 #pragma unroll
@@ -46,7 +47,7 @@ __device__ inline int cache_lookup(const CacheTable& C, const int32_t (&ids)[OT_
 #pragma unroll
       for (int i = 0; i < OT_MAX_NGRAM_LEN; ++i)
         if (i < L) same = same && (slot[2 + i] == ids[i]);
-      if (same) return slot[1];
+      if (same) return (int)h;
     }
     h = (h + 1) & C.mask;
   }
@@ -98,7 +99,7 @@ __global__ __launch_bounds__(768) void translate_accept_kernel(StepArgs a) {
   const int k = a.row_off[b + 1] - r0 - 1;
   const int q0 = r0 - b;
   __shared__ int32_t s_dm[64];
-  __shared__ unsigned long long s_hit[64];   // (length << 32) | target of the longest cache hit starting here, 0 = none
+  __shared__ unsigned long long s_hit[64];   // (length << 60) | (slot << 32) | target of the longest cache hit starting here, 0 = none
   __shared__ int32_t s_tok[64], s_start[64], s_len[64];
   __shared__ double s_logq[64], s_lq[64];
   __shared__ float s_zq[64];
@@ -148,8 +149,11 @@ __global__ __launch_bounds__(768) void translate_accept_kernel(StepArgs a) {
             in_range = in_range && ids[i] >= 0 && ids[i] < a.V_d;
           }
           if (in_range) {
-            const int t = cache_lookup(a.cache, ids, L);
-            if (t >= 0) atomicMax(&s_hit[s], ((unsigned long long)L << 32) | (unsigned int)t);
+            const int slot = cache_lookup(a.cache, ids, L);
+            if (slot >= 0) {
+              const unsigned int t = (unsigned int)a.cache.slots[(size_t)slot * a.cache.stride + 1];
+              atomicMax(&s_hit[s], ((unsigned long long)L << 60) | ((unsigned long long)slot << 32) | t);
+            }
           }
         }
       }
@@ -194,7 +198,11 @@ __global__ __launch_bounds__(768) void translate_accept_kernel(StepArgs a) {
     while (s < k) {
       int L, t;
       if (s_hit[s] != 0ull) {
-        L = (int)(s_hit[s] >> 32); t = (int)(s_hit[s] & 0xFFFFFFFFull); ++hits;
+        L = (int)(s_hit[s] >> 60); t = (int)(s_hit[s] & 0xFFFFFFFFull); ++hits;
+        // use statistics of the entry (Appendix, cache eviction): one more use, last used now
+        const unsigned int slot = (unsigned int)(s_hit[s] >> 32) & 0x0FFFFFFFu;
+        atomicAdd(&a.cache.uses[slot], 1u);
+        a.cache.last_used[slot] = a.cache.clock;
       } else {
         t = s_dm[s];
         L = 1;

@@ -7,15 +7,19 @@
 #include <new>
 #include <vector>
 
-#include "otv_internal.h"
+#include "otv_host.h"
 
 using namespace otv;
 
 namespace {
 
 thread_local char g_err[512] = "";
+constexpr int kProfileCapacity = 1024;   // steps whose events can be pending between two profile reads
+constexpr int kEventsPerStep = OT_N_STAGES + 1;
 
-int fail(int code, const char* fmt, ...) {
+}  // namespace
+
+int ot_fail(int code, const char* fmt, ...) {
   va_list ap;
   va_start(ap, fmt);
   vsnprintf(g_err, sizeof(g_err), fmt, ap);
@@ -23,43 +27,10 @@ int fail(int code, const char* fmt, ...) {
   return code;
 }
 
-int fail_hip(hipError_t e, const char* what) {
-  return fail(OT_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
-}
+int ot_fail_hip(hipError_t e, const char* what) { return ot_fail(OT_ERR_HIP, "%s: %s", what, hipGetErrorString(e)); }
 
-constexpr int kProfileCapacity = 1024;   // steps whose events can be pending between two profile reads
-constexpr int kEventsPerStep = OT_N_STAGES + 1;
-
-}  // namespace
-
-struct ot_ctx {
-  int32_t d = 0, V_t = 0, V_d = 0, max_batch = 0, max_k = 0, dtype = 0, max_ngram_len = 0;
-  int32_t max_rows = 0, max_K = 0, Kp = 0, Vp = 0, ncht = 0, nchd = 0, ntiles = 0;
-  hipStream_t stream = nullptr;
-  int device = 0;
-  std::vector<void*> allocs;
-  uint16_t* Wp = nullptr;
-  uint16_t* zeros = nullptr;          // 64 zero bytes: source of the K tail in the LM-head's hidden slices
-  float* Wf = nullptr;
-  int32_t *dmap = nullptr, *tmap = nullptr;
-  float* Z = nullptr;
-  float *tpart_max = nullptr, *dpart_max = nullptr, *row_max = nullptr, *drow_max = nullptr;
-  double *tpart_sum = nullptr, *dpart_sum = nullptr, *row_sum = nullptr, *drow_sum = nullptr;
-  int32_t *tpart_arg = nullptr, *dpart_arg = nullptr, *row_arg = nullptr, *drow_arg = nullptr;
-  double *tile_r = nullptr, *tile_p = nullptr;
-  FinalInfo* fin = nullptr;
-  // profiling
-  bool profiling = false;
-  std::vector<hipEvent_t> events;   // kEventsPerStep per pending step
-  int pending = 0;
-};
-
-struct ot_ngram_cache {
-  ot_ctx* owner = nullptr;
-  int32_t* slots = nullptr;
-  uint32_t mask = 0;
-  int32_t stride = 0, max_len = 0, n_entries = 0;
-};
+#define fail ot_fail
+#define fail_hip ot_fail_hip
 
 namespace {
 
@@ -168,71 +139,7 @@ void ot_verify_destroy(ot_ctx* ctx) {
   free_ctx(ctx);
 }
 
-int ot_ngram_cache_build(ot_ctx* ctx, int32_t n_entries, const int32_t* key_off, const int32_t* key_ids,
-                         const int32_t* target_ids, ot_ngram_cache** out) {
-  if (out) *out = nullptr;
-  if (!ctx || !out) return fail(OT_ERR_NULL, "ot_ngram_cache_build: ctx and out must not be NULL");
-  if (n_entries < 0) return fail(OT_ERR_SHAPE, "ot_ngram_cache_build: n_entries < 0");
-  if (n_entries > 0 && (!key_off || !key_ids || !target_ids)) return fail(OT_ERR_NULL, "ot_ngram_cache_build: NULL entry arrays");
-  if (n_entries > (1 << 28)) return fail(OT_ERR_SHAPE, "ot_ngram_cache_build: too many entries");
-  const int stride = 2 + ctx->max_ngram_len;
-  for (int32_t e = 0; e < n_entries; ++e) {
-    const int64_t len = (int64_t)key_off[e + 1] - key_off[e];
-    if (key_off[e] < 0 || len < 2 || len > ctx->max_ngram_len)
-      return fail(OT_ERR_NGRAM, "ot_ngram_cache_build: entry %d has length %lld, allowed 2..%d", e, (long long)len, ctx->max_ngram_len);
-    for (int64_t i = key_off[e]; i < key_off[e + 1]; ++i)
-      if (key_ids[i] < 0 || key_ids[i] >= ctx->V_d)
-        return fail(OT_ERR_NGRAM, "ot_ngram_cache_build: entry %d holds draft id %d outside [0, V_d)", e, key_ids[i]);
-    if (target_ids[e] < 0 || target_ids[e] >= ctx->V_t)
-      return fail(OT_ERR_NGRAM, "ot_ngram_cache_build: entry %d maps to target id %d outside [0, V_t)", e, target_ids[e]);
-  }
-  uint32_t cap = 16;
-  while (cap < 2u * (uint32_t)n_entries) cap <<= 1;
-  std::vector<int32_t> table;
-  try {
-    table.assign((size_t)cap * stride, 0);
-  } catch (const std::bad_alloc&) {
-    return fail(OT_ERR_NOMEM, "ot_ngram_cache_build: host allocation failed");
-  }
-  const uint32_t mask = cap - 1;
-  for (int32_t e = 0; e < n_entries; ++e) {
-    const int32_t* ids = key_ids + key_off[e];
-    const int len = key_off[e + 1] - key_off[e];
-    uint32_t h = hash_ngram(ids, len) & mask;
-    for (;;) {
-      int32_t* slot = &table[(size_t)h * stride];
-      if (slot[0] == 0) {
-        slot[0] = len;
-        slot[1] = target_ids[e];
-        std::memcpy(slot + 2, ids, sizeof(int32_t) * len);
-        break;
-      }
-      if (slot[0] == len && std::memcmp(slot + 2, ids, sizeof(int32_t) * len) == 0) {
-        slot[1] = target_ids[e];          // equal key: the later entry wins
-        break;
-      }
-      h = (h + 1) & mask;
-    }
-  }
-  ot_ngram_cache* c = new (std::nothrow) ot_ngram_cache();
-  if (!c) return fail(OT_ERR_NOMEM, "ot_ngram_cache_build: host allocation failed");
-  c->owner = ctx; c->mask = mask; c->stride = stride; c->max_len = ctx->max_ngram_len; c->n_entries = n_entries;
-  hipError_t e = hipMalloc(reinterpret_cast<void**>(&c->slots), table.size() * sizeof(int32_t));
-  if (e != hipSuccess) { (void)hipGetLastError(); delete c; return fail(OT_ERR_NOMEM, "ot_ngram_cache_build: device allocation failed"); }
-  e = hipMemcpy(c->slots, table.data(), table.size() * sizeof(int32_t), hipMemcpyHostToDevice);
-  if (e != hipSuccess) { (void)hipFree(c->slots); delete c; return fail_hip(e, "ot_ngram_cache_build: copy"); }
-  *out = c;
-  return OT_OK;
-}
-
-void ot_ngram_cache_destroy(ot_ngram_cache* cache) {
-  if (!cache) return;
-  if (cache->owner) (void)hipStreamSynchronize(cache->owner->stream);
-  (void)hipFree(cache->slots);
-  delete cache;
-}
-
-static int step_impl(ot_ctx* ctx, const ot_ngram_cache* cache, const ot_step_in* in, const float* ext_logits,
+static int step_impl(ot_ctx* ctx, ot_ngram_cache* cache, const ot_step_in* in, const float* ext_logits,
                      bool from_logits, ot_step_out* o) {
   if (!ctx || !in || !o) return fail(OT_ERR_NULL, "ot_verify_step: ctx, in and out must not be NULL");
   if (in->B < 0 || in->B > ctx->max_batch) return fail(OT_ERR_SHAPE, "ot_verify_step: B = %d exceeds max_batch = %d", in->B, ctx->max_batch);
@@ -260,8 +167,11 @@ static int step_impl(ot_ctx* ctx, const ot_ngram_cache* cache, const ot_step_in*
   a.row_off = in->row_off; a.hidden = in->hidden; a.draft_logits = in->draft_logits; a.draft_ids = in->draft_ids;
   a.temperature = in->temperature; a.draft_temperature = in->draft_temperature; a.seq_id = in->seq_id;
   a.dmap = ctx->dmap; a.tmap = ctx->tmap;
+  if (cache) cache->clock += 1;             // one tick of the cache's logical time per step that is given the cache
   if (cache && cache->n_entries > 0) {
-    a.cache.slots = cache->slots; a.cache.mask = cache->mask; a.cache.stride = cache->stride; a.cache.max_len = cache->max_len;
+    a.cache.slots = cache->d_slots; a.cache.mask = cache->mask; a.cache.stride = cache->stride;
+    a.cache.max_len = cache->max_len; a.cache.uses = cache->d_uses; a.cache.last_used = cache->d_last;
+    a.cache.clock = cache->clock;
   }
   a.Z = from_logits ? ext_logits : ctx->Z;
   a.ldz = ctx->V_t;
@@ -311,11 +221,11 @@ static int step_impl(ot_ctx* ctx, const ot_ngram_cache* cache, const ot_step_in*
   return OT_OK;
 }
 
-int ot_verify_step(ot_ctx* ctx, const ot_ngram_cache* cache, const ot_step_in* in, ot_step_out* out) {
+int ot_verify_step(ot_ctx* ctx, ot_ngram_cache* cache, const ot_step_in* in, ot_step_out* out) {
   return step_impl(ctx, cache, in, nullptr, false, out);
 }
 
-int ot_verify_step_from_logits(ot_ctx* ctx, const ot_ngram_cache* cache, const ot_step_in* in,
+int ot_verify_step_from_logits(ot_ctx* ctx, ot_ngram_cache* cache, const ot_step_in* in,
                                const float* target_logits, ot_step_out* out) {
   return step_impl(ctx, cache, in, target_logits, true, out);
 }

@@ -1,0 +1,50 @@
+// Host-side structures shared by the translation units that implement the C ABI (api.hip, cache.hip).
+#pragma once
+
+#include <vector>
+
+#include "otv_internal.h"
+
+// Records the message ot_last_error() returns on this thread and hands back `code`.
+int ot_fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+int ot_fail_hip(hipError_t e, const char* what);
+
+struct ot_ctx {
+  int32_t d = 0, V_t = 0, V_d = 0, max_batch = 0, max_k = 0, dtype = 0, max_ngram_len = 0;
+  int32_t max_rows = 0, max_K = 0, Kp = 0, Vp = 0, ncht = 0, nchd = 0, ntiles = 0;
+  hipStream_t stream = nullptr;
+  int device = 0;
+  std::vector<void*> allocs;
+  uint16_t* Wp = nullptr;
+  uint16_t* zeros = nullptr;          // 64 zero bytes: source of the K tail in the LM-head's hidden slices
+  float* Wf = nullptr;
+  int32_t *dmap = nullptr, *tmap = nullptr;
+  float* Z = nullptr;
+  float *tpart_max = nullptr, *dpart_max = nullptr, *row_max = nullptr, *drow_max = nullptr;
+  double *tpart_sum = nullptr, *dpart_sum = nullptr, *row_sum = nullptr, *drow_sum = nullptr;
+  int32_t *tpart_arg = nullptr, *dpart_arg = nullptr, *row_arg = nullptr, *drow_arg = nullptr;
+  double *tile_r = nullptr, *tile_p = nullptr;
+  otv::FinalInfo* fin = nullptr;
+  // profiling
+  bool profiling = false;
+  std::vector<hipEvent_t> events;   // OT_N_STAGES + 1 per pending step
+  int pending = 0;
+};
+
+// One n-gram cache: an open-addressing table (linear probing) mirrored on the host, plus per-slot use statistics
+// that the translation kernel updates on the device.
+struct ot_ngram_cache {
+  ot_ctx* owner = nullptr;
+  int32_t capacity = 0;               // most entries the cache may hold
+  int32_t policy = OT_EVICT_NONE;
+  int32_t n_entries = 0;
+  int32_t stride = 0, max_len = 0;    // int32 words per slot, longest key
+  uint32_t mask = 0;                  // slots - 1
+  uint32_t clock = 0;                 // logical time: +1 per step that uses the cache and per insert call
+  uint64_t next_seq = 0;              // insertion numbers
+  std::vector<int32_t> table;         // host mirror of the slots
+  std::vector<uint64_t> seq;          // host only: insertion number of the entry in each slot
+  int32_t* d_slots = nullptr;         // device copies
+  uint32_t* d_uses = nullptr;         // [slots] times the translation used the entry
+  uint32_t* d_last = nullptr;         // [slots] clock of the last use or (re-)insertion
+};

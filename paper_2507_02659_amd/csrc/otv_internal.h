@@ -21,9 +21,12 @@ inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 // Open addressing, linear probing.  Slot = { len, target, ids[max_len] } as int32; len == 0 marks an empty slot.
 struct CacheTable {
   const int32_t* slots;
-  uint32_t mask;      // capacity - 1, capacity a power of two >= 2 * entries
-  int32_t stride;     // int32 words per slot = 2 + max_len
+  uint32_t mask;       // slots - 1, slots a power of two >= 2 * capacity
+  int32_t stride;      // int32 words per slot = 2 + max_len
   int32_t max_len;
+  uint32_t* uses;      // [slots] incremented for every use of the entry by the translation scan
+  uint32_t* last_used; // [slots] set to `clock` on use
+  uint32_t clock;      // logical time of this step
 };
 
 __host__ __device__ inline uint32_t hash_ngram(const int32_t* ids, int len) {
