@@ -5,15 +5,17 @@
 // the d x V_t weights from HBM exactly once, not by the matrix cores.  The design follows from that:
 //   * W is re-tiled once at init into the register layout of v_mfma_f32_16x16x32_bf16 operands: the fragment for
 //     16 vocabulary columns x 32 hidden indices is 64 lanes x 16 bytes, stored contiguously, and the four
-//     fragments one wavefront needs per 32-deep step are adjacent.  A wavefront therefore streams its 64 columns
-//     with fully coalesced 16-byte loads straight into MFMA operand registers: no LDS round trip, no transpose.
+//     fragments of 64 adjacent columns per 32-deep step are adjacent.  A wavefront streams the fragments of its
+//     columns with fully coalesced 1 KB loads: no transpose anywhere.
 //   * Every weight is used by exactly one wavefront, which keeps accumulators for ALL rows of the M-block
-//     (up to 9 x 16 rows x 64 columns = 144 registers), so W never has to be re-read for another row tile.
-//   * The hidden rows, shared by the wavefronts of a workgroup, go through LDS in 128-deep double-buffered slices
-//     filled by direct global->LDS loads (swizzled rows: conflict-free 16-byte reads); each hidden fragment read
-//     from LDS feeds four MFMAs.
-//   * Weight fragments are prefetched PF 32-deep steps ahead in registers, so that the one barrier per slice never
-//     waits on HBM latency.
+//     (up to 9 x 16 rows), so W never has to be re-read for another row tile.
+//   * From 17 rows on, both operands travel by direct global->LDS loads.  The hidden rows, shared by the wavefronts
+//     of a workgroup, go through 128-deep double-buffered slices (swizzled rows: conflict-free 16-byte reads); each
+//     hidden fragment read from LDS feeds NW MFMAs.  The weight fragments go through a wavefront-private ring four
+//     steps deep, so that the one barrier per slice never waits on HBM latency.
+//   * All waits on the load counter are written by hand, by number (loads complete in issue order), and workgroup
+//     barriers carry no fence: with direct-to-LDS loads in flight every wait the compiler adds itself is a full
+//     drain of the counter, which would empty the weight pipeline at every slice.
 // Operand roles: the weight fragment is MFMA operand A and the hidden fragment operand B, so a lane ends up with
 // four consecutive vocabulary columns of one row and stores them as one float4.
 #include "otv_internal.h"
@@ -51,7 +53,7 @@ __global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict_
 }
 
 // ---------------------------------------------------------------------------------------------------------------
-// Wide kernel: M-blocks of up to MT*16 rows.  WPG wavefronts per workgroup, each owning 64 columns over the whole
+// Wide kernel: M-blocks of up to MT*16 rows.  WPG wavefronts per workgroup, each owning NW*16 columns over the whole
 // hidden dimension.  The hidden slice (KC columns of all rows of the M-block) is double-buffered in LDS and filled
 // by direct global->LDS loads (no staging registers): the next slice is requested before the current one feeds the
 // MFMAs, and one barrier per slice hands the buffers over.  LDS rows are unpadded; the 16-byte chunks of a row are
@@ -63,6 +65,15 @@ typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 // s_waitcnt immediate (gfx9 encoding) that waits until at most N vector-memory loads are outstanding and nothing else
 constexpr int vmcnt_imm(int n) { return (n & 0xF) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
 
+// Workgroup barrier without the memory fence of __syncthreads().  The fence makes the compiler drain every
+// outstanding vector-memory load (it cannot tell a direct-to-LDS load that must be visible from a register prefetch
+// that need not be), which would empty the prefetch pipelines at every hand-over.  The kernels below wait by count for
+// exactly the loads that have to be visible (s_waitcnt above) and then meet here; LDS reads of the buffer that is
+// handed back have been consumed by MFMAs before a wavefront arrives.
+__device__ inline void wg_barrier() { __builtin_amdgcn_s_barrier(); }
+
+constexpr int gcd_c(int a, int b) { return b == 0 ? a : gcd_c(b, a % b); }
+
 template <int MT, int PF, int WPG, int KC, int NW>
 __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16_t* __restrict__ H, int M, int d,
                                                                     const uint4* __restrict__ Wp, int nks,
@@ -73,24 +84,40 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
   constexpr int kCPR = KC / 8;                     // 16-byte chunks per slice row
   constexpr int kSliceChunks = MT * 16 * kCPR;
   constexpr int kDma = (kSliceChunks + WPG * 64 - 1) / (WPG * 64);
+  constexpr int kDmaMin = kSliceChunks / (WPG * 64);   // direct loads per slice that every wavefront issues
   constexpr int kPatchRow = NW * 16 + 4;           // floats per padded row of the epilogue patch
-  static_assert(kKSteps % PF == 0 && kGemmKPad % KC == 0 && kCPR >= 16 && kKSteps * NW < 64, "slice geometry");
+  // steps per trip of the main loop: whole pairs of slices (buffers A, B) and whole turns of the weight ring, so
+  // that both the buffer and the ring array of every step are known at compile time
+  constexpr int kUnroll = 2 * kKSteps * PF / gcd_c(2 * kKSteps, PF);
+  static_assert(PF % kKSteps == 0 && PF <= 6, "a weight fetch is used a whole number of slices later");
+  static_assert(kGemmKPad % KC == 0 && (kCPR == 8 || kCPR == 16), "slice geometry");
+  static_assert((PF - 1) * NW + (PF / kKSteps) * kDma + NW < 64, "the load counter has 6 bits");
   static_assert(NW == 1 || NW == 2 || NW == 4, "a wavefront owns 16, 32 or 64 columns");
   __shared__ __attribute__((aligned(16))) uint16_t sA[MT * 16 * KC];
   __shared__ __attribute__((aligned(16))) uint16_t sB[MT * 16 * KC];
   __shared__ __attribute__((aligned(16))) float sPatch[WPG][16 * kPatchRow];   // epilogue: one 16-row tile per wavefront
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  // The weight fragments travel by direct global->LDS loads as well, into a ring of PF steps: one array per step (so
+  // that the compiler can tell them apart), each wavefront using its own NW KB of every array.  A register prefetch
+  // next to direct-to-LDS loads would make the compiler drain the load counter at each first use of a register.
+  constexpr int kRing = WPG * NW * 64;
+  __shared__ uint4 sW0[kRing], sW1[kRing], sW2[PF > 2 ? kRing : 1], sW3[PF > 3 ? kRing : 1], sW4[PF > 4 ? kRing : 1],
+      sW5[PF > 5 ? kRing : 1];
+  static_assert((WPG & (WPG - 1)) == 0, "the mask below tells the compiler the range of the wavefront index");
+  const int tid = threadIdx.x, wave = (tid >> 6) & (WPG - 1), lane = tid & 63;
   // Workgroup id -> (column tile, M-block).  Consecutive ids go round-robin to the 8 XCDs, each with its own L2; the
   // M-blocks of one column tile get ids that land on the same XCD back to back, so that when M needs several
   // blocks their weight streams coincide in that XCD's L2 and HBM is still read once.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int col_tile = (slot / m_blocks) * 8 + xcd, m_block = slot % m_blocks;
-  const int t16 = (col_tile * WPG + wave) * NW;       // first 16-column tile of this wavefront
   if (col_tile * WPG * NW >= n_wtiles * 4) return;    // padding of the id space (whole workgroup)
-  const bool active = t16 < n_wtiles * 4;
+  const int t16_own = (col_tile * WPG + wave) * NW;   // first 16-column tile of this wavefront
+  const bool active = t16_own < n_wtiles * 4;
+  // A wavefront past the last tile (only in the last workgroup) multiplies the last tile again and stores nothing:
+  // the main loop then has no wavefront-dependent branch and every wavefront issues the same loads in the same order.
+  const int t16 = active ? t16_own : n_wtiles * 4 - NW;
   const int row0 = m_block * (MT * 16);
   // fragment (16-column tile t, step ks) sits at 16-byte unit (((t/4) * nks + ks) * 4 + t%4) * 64 + lane
-  const uint4* wp = Wp + ((int64_t)((active ? t16 : 0) / 4) * nks * 4 + (t16 % 4)) * 64 + lane;
+  const uint4* wp = Wp + ((int64_t)(t16 / 4) * nks * 4 + (t16 % 4)) * 64 + lane;
 
   f32x4 acc[MT][NW];
 #pragma unroll
@@ -98,15 +125,21 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
 #pragma unroll
     for (int nw = 0; nw < NW; ++nw) acc[mt][nw] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // request slice kc (in 32-column steps) into buffer s: chunk q of the buffer holds logical chunk (q%kCPR)^(row&15)
-  auto request = [&](int kc, uint16_t* s) {
+  // Swizzle key of a row: the 16-byte chunks of a row are XORed with it.  Rows of 256 bytes: the row index; rows of
+  // 128 bytes: rows r and r+8 would meet in the same banks, so bit 3 is folded into bit 0.
+  auto row_key = [](int row) { return kCPR == 16 ? (row & 15) : ((row ^ (row >> 3)) & 7); };
+  // request slice kc (in 32-column steps) into buffer s: chunk q of the buffer holds logical chunk (q%kCPR)^key(row).
+  // A request past the end of K re-reads the last slice, so that every slice issues the same number of loads and
+  // the in-order load counter can be waited on by number.
+  auto request = [&](int kc_want, uint16_t* s) {
+    const int kc = min(kc_want, nks - kKSteps);
 #pragma unroll
     for (int j = 0; j < kDma; ++j) {
       const int q0 = (j * WPG + wave) * 64;        // wave-uniform
       if (q0 < kSliceChunks) {
         const int q = q0 + lane;
         const int row = q / kCPR, pc = q % kCPR;
-        const int lc = pc ^ (row & 15);
+        const int lc = pc ^ row_key(row);
         const int gr = min(row0 + row, M - 1);     // rows past M are never stored: any valid row will do
         const int gk = kc * 32 + lc * 8;
         const uint16_t* src = gk < d ? H + (int64_t)gr * d + gk : zeros;   // the padded tail of K must read as zero
@@ -114,61 +147,78 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
       }
     }
   };
+  auto ring = [&](int s) -> uint4* {
+    return (s == 0 ? sW0 : s == 1 ? sW1 : s == 2 ? sW2 : s == 3 ? sW3 : s == 4 ? sW4 : sW5) + wave * (NW * 64);
+  };
+  // fetch the fragments of step kf into this wavefront's part of ring array s
+  auto fetch_w = [&](int kf, int s) {
+#pragma unroll
+    for (int nw = 0; nw < NW; ++nw)
+      __builtin_amdgcn_global_load_lds((glb_ptr_t)(wp + ((int64_t)kf * 4 + nw) * 64), (lds_ptr_t)(ring(s) + nw * 64), 16,
+                                       0, 0);
+  };
 
   request(0, sA);
-  uint4 bq[PF][NW];
 #pragma unroll
-  for (int s = 0; s < PF; ++s)
-#pragma unroll
-    for (int nw = 0; nw < NW; ++nw) bq[s][nw] = (active && s < nks) ? wp[(s * 4 + nw) * 64] : make_uint4(0, 0, 0, 0);
+  for (int s = 0; s < PF; ++s) fetch_w(min(s, nks - 1), s);
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-  __syncthreads();
+  wg_barrier();
 
   const int a_row = lane & 15, a_grp = lane >> 4;
-  auto compute = [&](const uint16_t* hs, int kc) {
-    if (!active) return;
+  // one slice out of buffer hs; kc = its first step, s0 = ring array of that step (compile-time after unrolling)
+  auto compute = [&](const uint16_t* hs, int kc, int s0) {
 #pragma unroll
     for (int ks = 0; ks < kKSteps; ++ks) {
       const int kk = kc + ks;
+      const int rs = (s0 + ks) % PF;
+      // This step's weight fragments were requested PF steps ago; since then PF-1 refills and PF/kKSteps hidden slices
+      // were requested, so they have landed once no more loads than that are outstanding.  Waiting by number here
+      // (with an instruction between the wait and the read) also spares the compiler from inserting its own wait,
+      // which with direct-to-LDS loads in flight is always a full drain.
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm((PF - 1) * NW + (PF / kKSteps) * kDmaMin));
+      asm volatile("s_nop 0");
+      __builtin_amdgcn_sched_barrier(0);
+      uint4 bw[NW];
+#pragma unroll
+      for (int nw = 0; nw < NW; ++nw) bw[nw] = ring(rs)[nw * 64 + lane];
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        const int pc = (ks * 4 + a_grp) ^ a_row;
+        const int pc = (ks * 4 + a_grp) ^ row_key(a_row);
         const uint4 hv = *reinterpret_cast<const uint4*>(&hs[(mt * 16 + a_row) * KC + pc * 8]);
         const bf16x8 hf = __builtin_bit_cast(bf16x8, hv);
 #pragma unroll
         for (int nw = 0; nw < NW; ++nw) {
-          acc[mt][nw] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bq[ks % PF][nw]), hf,
-                                                                acc[mt][nw], 0, 0, 0);
+          acc[mt][nw] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, bw[nw]), hf, acc[mt][nw],
+                                                                0, 0, 0);
         }
       }
-      // the slot is free again: refill it with the fragments PF steps ahead
-      if (kk + PF < nks) {
-#pragma unroll
-        for (int nw = 0; nw < NW; ++nw) bq[ks % PF][nw] = wp[((int64_t)(kk + PF) * 4 + nw) * 64];
-      }
+      // the ring array is free again: refill it with the fragments PF steps ahead (past the end: the last ones again)
+      fetch_w(min(kk + PF, nks - 1), rs);
       __builtin_amdgcn_sched_barrier(0);   // keep the next step's LDS reads from being hoisted (register budget)
     }
   };
   // Loads complete in issue order, so once at most kKSteps*NW loads (the weight fragments requested during the slice)
   // are outstanding, this wavefront's part of the next hidden slice has landed in LDS.
-  auto hand_over = [&](int kc) {
+  auto hand_over = [&]() {
     __builtin_amdgcn_sched_barrier(0);
-    if (active && kc + kKSteps - 1 + PF < nks) __builtin_amdgcn_s_waitcnt(vmcnt_imm(kKSteps * NW));
-    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-    __syncthreads();
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(kKSteps * NW));
+    wg_barrier();
   };
 
-  for (int kc = 0; kc < nks; kc += 2 * kKSteps) {
-    const bool more = kc + kKSteps < nks;
-    if (more) request(kc + kKSteps, sB);
-    __builtin_amdgcn_sched_barrier(0);
-    compute(sA, kc);
-    hand_over(kc);
-    if (!more) break;
-    if (kc + 2 * kKSteps < nks) request(kc + 2 * kKSteps, sA);
-    __builtin_amdgcn_sched_barrier(0);
-    compute(sB, kc + kKSteps);
-    hand_over(kc + kKSteps);
+  for (int base = 0; base < nks; base += kUnroll) {
+    bool done = false;
+#pragma unroll
+    for (int p = 0; p < kUnroll / kKSteps; ++p) {
+      if (!done) {
+        const int kc = base + p * kKSteps;
+        request(kc + kKSteps, (p & 1) ? sA : sB);
+        __builtin_amdgcn_sched_barrier(0);
+        compute((p & 1) ? sB : sA, kc, (p * kKSteps) % PF);
+        hand_over();
+        done = kc + kKSteps >= nks;
+      }
+    }
+    if (done) break;
   }
   if (!active) return;
   // Epilogue.  After the MFMAs a lane holds Z[row0 + mt*16 + lane%16][(t16 + nw)*16 + 4*(lane/16) + 0..3]: 64-byte
@@ -322,9 +372,10 @@ hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* W
                        reinterpret_cast<const uint4*>(Wp), nks, Z, V_t, ldz);
     return hipGetLastError();
   }
-  if (tiles <= 2) return launch_wide<2, 4, 4, 128, 4>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
-  if (tiles <= 4) return launch_wide<4, 4, 4, 128, 4>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
-  if (tiles <= 6) return launch_wide<6, 4, 4, 128, 4>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
+  if (tiles <= 2) return launch_wide<2, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
+  if (tiles <= 4) return launch_wide<4, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
+  if (tiles <= 6) return launch_wide<6, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
+  // 144 rows per M-block; more rows run as several M-blocks per column tile (their weight streams meet in one L2)
   return launch_wide<9, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
 }
 

@@ -40,7 +40,8 @@ def _run_and_compare(case, *, expect_exact_fraction=0.0, max_divergent=None):
 
 # --------------------------------------------------------------------------- LM head (MFMA) against float64
 @pytest.mark.parametrize("M,d,V_t", [(1, 256, 1024), (5, 320, 1000), (16, 256, 4100), (17, 512, 2048), (48, 128, 777),
-                                     (100, 384, 3000), (144, 256, 2304), (150, 256, 1500), (300, 136, 1111)])
+                                     (100, 384, 3000), (144, 256, 2304), (150, 256, 1500), (300, 136, 1111),
+                                     (257, 192, 2000), (512, 256, 5000), (640, 64, 300)])
 def test_lm_head_logits_bf16(M, d, V_t):
     ov, ot, Verifier, parity = _imports()
     k = M - 1 if M - 1 <= 63 else None
