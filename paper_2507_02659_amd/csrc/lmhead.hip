@@ -70,7 +70,20 @@ constexpr int vmcnt_imm(int n) { return (n & 0xF) | (7 << 4) | (15 << 8) | ((n >
 // that need not be), which would empty the prefetch pipelines at every hand-over.  The kernels below wait by count for
 // exactly the loads that have to be visible (s_waitcnt above) and then meet here; LDS reads of the buffer that is
 // handed back have been consumed by MFMAs before a wavefront arrives.
-__device__ inline void wg_barrier() { __builtin_amdgcn_s_barrier(); }
+// The empty asm statements keep the compiler from moving memory accesses across the barrier.
+__device__ inline void wg_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+// Barrier that publishes this wavefront's LDS writes (all LDS operations done) without touching the load counter.
+__device__ inline void lds_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0), vmcnt and expcnt unconstrained
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
 
 constexpr int gcd_c(int a, int b) { return b == 0 ? a : gcd_c(b, a % b); }
 
@@ -79,7 +92,8 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
                                                                     const uint4* __restrict__ Wp, int nks,
                                                                     int n_wtiles, float* __restrict__ Z, int V_t,
                                                                     int64_t ldz, int vec_store,
-                                                                    const uint16_t* __restrict__ zeros, int m_blocks) {
+                                                                    const uint16_t* __restrict__ zeros, int m_blocks,
+                                                                    FusedStats fs) {
   constexpr int kKSteps = KC / 32;                 // MFMA steps per slice
   constexpr int kCPR = KC / 8;                     // 16-byte chunks per slice row
   constexpr int kSliceChunks = MT * 16 * kCPR;
@@ -102,6 +116,13 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
   constexpr int kRing = WPG * NW * 64;
   __shared__ uint4 sW0[kRing], sW1[kRing], sW2[PF > 2 ? kRing : 1], sW3[PF > 3 ? kRing : 1], sW4[PF > 4 ? kRing : 1],
       sW5[PF > 5 ? kRing : 1];
+  // fused row statistics: row offsets and temperatures of the sequences (staged by direct loads in the prologue),
+  // and the exponent scale log2(e)/T of each row of the M-block
+  __shared__ int32_t sRowOff[kFusedMaxB + 1];
+  __shared__ float sTemp[kFusedMaxB + 1];
+  __shared__ float sScale[MT * 16];
+  static_assert(WPG * MT * 64 * 8 <= MT * 16 * KC * 2, "the per-lane row statistics reuse the two hidden buffers");
+  static_assert(WPG * 64 >= MT * 16 && WPG * 64 >= kFusedMaxB + 1, "one thread per row / per sequence");
   static_assert((WPG & (WPG - 1)) == 0, "the mask below tells the compiler the range of the wavefront index");
   const int tid = threadIdx.x, wave = (tid >> 6) & (WPG - 1), lane = tid & 63;
   // Workgroup id -> (column tile, M-block).  Consecutive ids go round-robin to the 8 XCDs, each with its own L2; the
@@ -161,6 +182,14 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
   request(0, sA);
 #pragma unroll
   for (int s = 0; s < PF; ++s) fetch_w(min(s, nks - 1), s);
+  if (fs.fmax) {   // 4-byte direct loads: lane i of a wavefront fills entry 64*wave + i
+    if (wave * 64 <= fs.B) {
+      __builtin_amdgcn_global_load_lds((glb_ptr_t)(fs.row_off + min(tid, fs.B)), (lds_ptr_t)(sRowOff + wave * 64), 4, 0,
+                                       0);
+      __builtin_amdgcn_global_load_lds((glb_ptr_t)(fs.temperature + min(tid, fs.B - 1)), (lds_ptr_t)(sTemp + wave * 64),
+                                       4, 0, 0);
+    }
+  }
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
   wg_barrier();
 
@@ -219,6 +248,79 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
       }
     }
     if (done) break;
+  }
+  if (fs.fmax) {
+    // Row statistics of this workgroup's column tile, from the accumulators: per row the maximum, its lowest column
+    // and sum exp((z - max)/T), first per wavefront (NW*16 columns), then merged over the wavefronts; one partial per
+    // row and column tile goes to memory.  All LDS buffers of the main loop are free: every wavefront has passed the
+    // barrier that followed its last slice (the weight ring may still receive the surplus refills; it is not used).
+    float* st_max = reinterpret_cast<float*>(sA);
+    float* st_sum = st_max + WPG * MT * 64;
+    int32_t* st_arg = reinterpret_cast<int32_t*>(sB);
+    if (tid < MT * 16) {
+      const int row = min(row0 + tid, M - 1);
+      int lo = 0, hi = fs.B - 1;                    // sequence that owns the row: last b with row_off[b] <= row
+      while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (sRowOff[mid] <= row) lo = mid; else hi = mid - 1;
+      }
+      const float T_b = sTemp[lo];
+      sScale[tid] = T_b > 0.f ? 1.4426950408889634f / T_b : 1.4426950408889634f;
+    }
+    lds_barrier();
+    // every lane reduces its own NW*4 values of a row (no cross-lane traffic) and parks the partial in LDS; only a
+    // wavefront that reaches past column V_t (or repeats the last tile) has to mask
+    const int n_valid = active ? V_t - (t16 * 16 + 4 * (lane >> 4)) : 0;   // this lane's columns n0 + 16*nw + e < V_t
+    const bool all_valid = __builtin_amdgcn_readfirstlane(active && (t16 + NW) * 16 <= V_t);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const float sc = sScale[mt * 16 + (lane & 15)];
+      float v[NW * 4];
+#pragma unroll
+      for (int nw = 0; nw < NW; ++nw)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          v[nw * 4 + e] = (all_valid || nw * 16 + e < n_valid) ? acc[mt][nw][e] : -INFINITY;
+      float best = v[0];
+      int bi = 0;
+#pragma unroll
+      for (int i = 1; i < NW * 4; ++i)              // ascending columns: the first maximum is kept
+        if (v[i] > best) { best = v[i]; bi = i; }
+      const int barg = best == -INFINITY ? 0x7FFFFFFF : t16 * 16 + 4 * (lane >> 4) + (bi >> 2) * 16 + (bi & 3);
+      const float nb = best == -INFINITY ? 0.f : -best * sc;
+      float sum = 0.f;
+#pragma unroll
+      for (int i = 0; i < NW * 4; ++i) sum += __builtin_amdgcn_exp2f(fmaf(v[i], sc, nb));   // masked: exp2(-inf) = 0
+      const int at = (wave * (MT * 16) + mt * 16 + (lane & 15)) * 4 + (lane >> 4);
+      st_max[at] = best; st_sum[at] = sum; st_arg[at] = barg;
+    }
+    lds_barrier();
+    // one thread per row merges the WPG x 4 partials in a fixed order and writes the tile's partial
+    if (tid < MT * 16 && row0 + tid < M) {
+      const float sc = sScale[tid];
+      float best = -INFINITY;
+      int barg = 0x7FFFFFFF;
+#pragma unroll
+      for (int w = 0; w < WPG; ++w) {
+        const f32x4 m4 = *reinterpret_cast<const f32x4*>(&st_max[(w * (MT * 16) + tid) * 4]);
+        const int4 a4 = *reinterpret_cast<const int4*>(&st_arg[(w * (MT * 16) + tid) * 4]);
+        const int a[4] = {a4.x, a4.y, a4.z, a4.w};
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          if (m4[g] > best || (m4[g] == best && a[g] < barg)) { best = m4[g]; barg = a[g]; }
+      }
+      float sum = 0.f;
+#pragma unroll
+      for (int w = 0; w < WPG; ++w) {
+        const f32x4 m4 = *reinterpret_cast<const f32x4*>(&st_max[(w * (MT * 16) + tid) * 4]);
+        const f32x4 s4 = *reinterpret_cast<const f32x4*>(&st_sum[(w * (MT * 16) + tid) * 4]);
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          if (m4[g] != -INFINITY) sum += s4[g] * __builtin_amdgcn_exp2f((m4[g] - best) * sc);
+      }
+      const int64_t o = (int64_t)(row0 + tid) * fs.nfine + col_tile;
+      fs.fmax[o] = best; fs.fsum[o] = sum; fs.farg[o] = barg;
+    }
   }
   if (!active) return;
   // Epilogue.  After the MFMAs a lane holds Z[row0 + mt*16 + lane%16][(t16 + nw)*16 + 4*(lane/16) + 0..3]: 64-byte
@@ -342,13 +444,13 @@ __global__ __launch_bounds__(256) void lmhead_f32_kernel(const float* __restrict
 
 template <int MT, int PF, int WPG, int KC, int NW>
 hipError_t launch_wide(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
-                       int64_t ldz, const uint16_t* zeros, hipStream_t stream) {
+                       int64_t ldz, const uint16_t* zeros, const FusedStats& fs, hipStream_t stream) {
   const int nks = Kp / 32, n_wtiles = Vp / kGemmColsPerWave;
   const int m_blocks = ceil_div(M, MT * 16);
   dim3 grid(ceil_div(ceil_div(n_wtiles * 4, WPG * NW), 8) * 8 * m_blocks), block(WPG * 64);
   const int vec_store = (ldz % 4 == 0) && (reinterpret_cast<uintptr_t>(Z) % 16 == 0);
   hipLaunchKernelGGL((lmhead_bf16_wide_kernel<MT, PF, WPG, KC, NW>), grid, block, 0, stream, H, M, d,
-                     reinterpret_cast<const uint4*>(Wp), nks, n_wtiles, Z, V_t, ldz, vec_store, zeros, m_blocks);
+                     reinterpret_cast<const uint4*>(Wp), nks, n_wtiles, Z, V_t, ldz, vec_store, zeros, m_blocks, fs);
   return hipGetLastError();
 }
 
@@ -362,21 +464,31 @@ hipError_t launch_pack_w_bf16(const uint16_t* W, int d, int V_t, uint16_t* Wp, i
   return hipGetLastError();
 }
 
+int lmhead_bf16_fused_partials(int M, int Vp) {
+  return M > 16 ? Vp / 256 : 0;      // the wide kernels own 256 columns per workgroup; the skinny kernel does not fuse
+}
+
 hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
-                              int64_t ldz, const uint16_t* zeros, hipStream_t stream) {
+                              int64_t ldz, const uint16_t* zeros, const FusedStats* fused, hipStream_t stream) {
   if (M == 0) return hipSuccess;
   const int tiles = ceil_div(M, 16);
+  FusedStats fs{};
+  if (fused && fused->fmax) {
+    if (fused->nfine != lmhead_bf16_fused_partials(M, Vp) || fused->nfine == 0 || fused->B < 1 || fused->B > kFusedMaxB)
+      return hipErrorInvalidValue;
+    fs = *fused;
+  }
   if (tiles <= 1) {
     const int nks = Kp / 32, n_wtiles = Vp / kGemmColsPerWave;
     hipLaunchKernelGGL((lmhead_bf16_skinny_kernel<4>), dim3(n_wtiles), dim3(512), 0, stream, H, M, d,
                        reinterpret_cast<const uint4*>(Wp), nks, Z, V_t, ldz);
     return hipGetLastError();
   }
-  if (tiles <= 2) return launch_wide<2, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
-  if (tiles <= 4) return launch_wide<4, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
-  if (tiles <= 6) return launch_wide<6, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
+  if (tiles <= 2) return launch_wide<2, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
+  if (tiles <= 4) return launch_wide<4, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
+  if (tiles <= 6) return launch_wide<6, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
   // 144 rows per M-block; more rows run as several M-blocks per column tile (their weight streams meet in one L2)
-  return launch_wide<9, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, stream);
+  return launch_wide<9, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
 }
 
 hipError_t launch_lmhead_f32(const float* H, int M, int d, const float* W, float* Z, int V_t, int64_t ldz,

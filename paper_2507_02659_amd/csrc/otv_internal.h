@@ -59,6 +59,19 @@ struct FinalInfo {
   double mx, invT, invS, mxq, invTd, invSq;
 };
 
+// Softmax partials emitted by the LM-head epilogue (one per row and column tile of the kernel), so that the logits
+// need not be read again for their row statistics.  fmax == nullptr: not wanted.
+constexpr int kFusedMaxB = 255;      // sequences whose row offsets and temperatures the LM-head kernel stages in LDS
+struct FusedStats {
+  const int32_t* row_off;            // [B + 1]
+  const float* temperature;          // [B]
+  int32_t B;
+  int32_t nfine;                     // partials per row (row stride of the arrays below)
+  float* fmax;                       // [M, nfine] maximum of the tile's logits of the row
+  float* fsum;                       // [M, nfine] sum of exp((z - fmax) / T_b) over the tile
+  int32_t* farg;                     // [M, nfine] lowest column holding fmax
+};
+
 struct StepArgs {
   // problem
   int32_t B, M, K, d, V_t, V_d, dtype, max_ngram_len;
@@ -80,6 +93,7 @@ struct StepArgs {
   int64_t ldz;
   int32_t ncht, nchd;    // statistic chunks per target / draft row
   float* tpart_max; double* tpart_sum; int32_t* tpart_arg;   // [M, ncht]
+  FusedStats fused;      // fused.nfine > 0: the LM head left fine partials; the statistics kernel merges them per row
   float* dpart_max; double* dpart_sum; int32_t* dpart_arg;   // [K, nchd]
   float* row_max; double* row_sum; int32_t* row_arg;         // [M]
   float* drow_max; double* drow_sum; int32_t* drow_arg;      // [K]
@@ -93,8 +107,13 @@ struct StepArgs {
 // ------------------------------------------------------------------------------------------------ launchers
 // Each returns the hipError_t of its launch.  All work goes to `stream`.
 hipError_t launch_pack_w_bf16(const uint16_t* W, int d, int V_t, uint16_t* Wp, int Kp, int Vp, hipStream_t stream);
+// Partials per row that launch_lmhead_bf16 emits for M rows of a Vp-column (padded) head; 0: that shape runs a
+// kernel without the fused statistics.
+int lmhead_bf16_fused_partials(int M, int Vp);
+// `fused` may be nullptr or have fmax == nullptr (no statistics); otherwise fused->nfine must be
+// lmhead_bf16_fused_partials(M, Vp) > 0 and fused->B <= kFusedMaxB.
 hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
-                              int64_t ldz, const uint16_t* zeros, hipStream_t stream);
+                              int64_t ldz, const uint16_t* zeros, const FusedStats* fused, hipStream_t stream);
 hipError_t launch_lmhead_f32(const float* H, int M, int d, const float* W, float* Z, int V_t, int64_t ldz,
                              hipStream_t stream);
 hipError_t launch_softmax_stats(const StepArgs& a, hipStream_t stream);

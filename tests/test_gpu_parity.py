@@ -116,6 +116,45 @@ def test_softmax_statistics(dtype, V_t, V_d):
         np.testing.assert_allclose(ws["draft_row_sumexp"][q0:q1], wantq, rtol=2e-6)
 
 
+@pytest.mark.parametrize("M,d,V_t", [(20, 256, 1000), (60, 128, 2304), (96, 192, 777), (144, 256, 4100), (300, 136, 1111)])
+def test_row_statistics_from_lm_head_epilogue(M, d, V_t):
+    """From 17 rows on the LM-head kernel emits the softmax partials itself (no second pass over the logits).
+
+    The oracle's logits are float64 and the kernel's fp32-accumulated, so the maximum is compared to 2e-5, the argmax
+    must be a column whose oracle logit is within that band of the oracle's maximum, and the sum of exponentials
+    (temperatures 1, 0.5, 2 and greedy rows) to 1e-4."""
+    ov, ot, Verifier, parity = _imports()
+    ks, left = [], M
+    while left > 0:
+        take = min(left, 40)
+        ks.append(take - 1)
+        left -= take
+    temps = [[1.0, 0.5, 0.0, 2.0][i % 4] for i in range(len(ks))]
+    spec = CaseSpec(name=f"fused_{M}x{d}x{V_t}", dtype="bf16", d=d, V_t=V_t, V_d=64, k=ks, temperature=temps,
+                    n_direct=32, data_seed=M * 11 + V_t, philox_seed=1)
+    case = make_case(spec)
+    assert case.M == M
+    _say(f"fused statistics case M={M} d={d} V_t={V_t}")
+    v = Verifier.for_case(case)
+    try:
+        inp = v.upload(case)
+        v.step(inp)
+        ws = v.workspace(case.M, case.K)
+    finally:
+        v.close()
+    Z = ov.lm_head_logits(case.hidden, case.W, "bf16")
+    zmax = Z.max(axis=1)
+    np.testing.assert_allclose(ws["row_max"], zmax, rtol=0, atol=2e-5)
+    arg = ws["row_argmax"].astype(np.int64)
+    assert arg.min() >= 0 and arg.max() < V_t
+    assert np.all(Z[np.arange(M), arg] >= zmax - 4e-5)
+    for b in range(case.B):
+        r0, r1 = case.row_off[b], case.row_off[b + 1]
+        T = float(case.temperature[b]) or 1.0
+        want = np.exp((Z[r0:r1] - Z[r0:r1].max(axis=1, keepdims=True)) / T).sum(axis=1)
+        np.testing.assert_allclose(ws["row_sumexp"][r0:r1], want, rtol=1e-4)
+
+
 # --------------------------------------------------------------------------- the five BASELINE configurations, full size
 @pytest.mark.parametrize("i,greedy", [(1, False), (2, False), (2, True), (3, False), (4, False), (5, False)])
 def test_baseline_configuration(i, greedy):
@@ -170,6 +209,13 @@ def test_ragged_maximum_k_and_empty_sequences():
     spec = CaseSpec(name="edge_k", dtype="bf16", d=128, V_t=5000, V_d=2000, k=[63, 0, 1, 63, 0], temperature=[1.0, 1.0, 0.0, 0.9, 0.0],
                     n_direct=1500, n_ngram=500, ngram_len=(2, 8), plant_cover=0.4, align=0.9, data_seed=88, philox_seed=6)
     _run_and_compare(make_case(spec))
+
+
+def test_more_sequences_than_the_lm_head_stages():
+    """Above 255 sequences the LM-head epilogue emits no statistics and the separate pass over the logits runs."""
+    spec = CaseSpec(name="edge_many_seqs", dtype="bf16", d=64, V_t=1300, V_d=600, k=[1, 0, 2] * 90, temperature=[1.0, 0.0, 0.7] * 90,
+                    n_direct=400, n_ngram=100, ngram_len=(2, 3), plant_cover=0.3, align=0.8, data_seed=90, philox_seed=8)
+    _run_and_compare(make_case(spec), max_divergent=4)
 
 
 def test_draft_temperature_variants():
