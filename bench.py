@@ -109,7 +109,10 @@ def main():
     gemm_bytes = lm_head_bytes(M, d, V_t) if esz == 2 else 4 * d * V_t + 4 * M * d + 4 * M * V_t
     gemm_s = stage_us["lm_head"] * 1e-6
     achieved = gemm_bytes / gemm_s / 1e9 if gemm_s > 0 else 0.0
-    stats_bytes = 4 * M * V_t + esz * K * V_d          # one pass over the target logits and the draft logits
+    # statistics pass: the draft logits once, plus either the target logits once or, when the LM-head epilogue has
+    # left per-tile softmax partials (bf16, more than 16 rows, at most 255 sequences), those partials
+    fused = esz == 2 and M > 16 and case.B <= 255 and not from_logits
+    stats_bytes = esz * K * V_d + (12 * M * ((V_t + 255) // 256) if fused else 4 * M * V_t)
     extra = {
         "stage_us": {k: round(x, 2) for k, x in stage_us.items()},
         "lm_head_tflops": round(2.0 * M * d * V_t / gemm_s / 1e12, 1) if gemm_s > 0 else None,
@@ -119,6 +122,24 @@ def main():
         "rows_per_s": round(M * args.steps / elapsed, 1),
         "step_hbm_bytes": gemm_bytes + stats_bytes + case.B * (4 * V_t + esz * V_d + 4 * V_t),
     }
+    extra["row_statistics"] = "lm_head epilogue" if fused else "separate pass over the logits"
+
+    # forward values of the hybrid distillation loss on the same batch (the pass that follows a step when the
+    # drafter is trained online): reverse KL on every direct-mapping token, NLL on n-gram tokens
+    if K > 0:
+        n_loss = 50
+        v.distill_loss(inp, from_logits=from_logits)
+        torch.cuda.synchronize()
+        t_l = time.perf_counter()
+        for _ in range(n_loss):
+            loss = v.distill_loss(inp, from_logits=from_logits, sync=False)
+        v.synchronize()
+        loss_us = 1e6 * (time.perf_counter() - t_l) / n_loss
+        loss = v.distill_loss(inp, from_logits=from_logits)
+        kl_rows = int(loss["n_dm"])
+        loss_bytes = kl_rows * (4 * V_t + 4 * V_t + esz * int((case.direct_map >= 0).sum()))   # logit row, inverse map, gathered draft row
+        extra["distill_loss"] = {"us_per_call": round(loss_us, 2), "kl_rows": kl_rows, "algorithmic_bytes": loss_bytes,
+                                 "gbs": round(loss_bytes / (loss_us * 1e-6) / 1e9, 1), "loss": round(loss["loss"], 6)}
     extra["step_frac_hbm_roofline"] = round(extra["step_hbm_bytes"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
 
     result = {

@@ -166,6 +166,48 @@ int ot_verify_step(ot_ctx* ctx, ot_ngram_cache* cache_or_null, const ot_step_in*
 int ot_verify_step_from_logits(ot_ctx* ctx, ot_ngram_cache* cache_or_null, const ot_step_in* in,
                                const float* target_logits, ot_step_out* out);
 
+/* ---- hybrid distillation loss, forward values --------------------------------------------------------- */
+/* Section "Cross-vocabulary Distillation", the loss equation: L = L_DM + lambda * L_N-gram, the expectation over
+ * drafted tokens d_i of  D_KL(q' || p)(t_i) * I_DM(d_i)  -  lambda * log q(d_i) * I_N-gram(d_i).
+ *   - a mapped token that came through the direct map carries the reverse KL between q', the draft distribution
+ *     of its position lifted into the target vocabulary (Eq. 2, not renormalised; the sum runs over q'(v) > 0),
+ *     and the target distribution p of its row;
+ *   - a mapped token that came from the n-gram cache carries NLL = -sum over its sub-tokens of ln q(d), or (
+ *     OT_NGRAM_TERM_APPROX_KL) the KL with Eq. 2's two overrides, times lambda: the constant `lambda`, or
+ *     (OT_LAMBDA_TARGET_PROB) the verified target probability p(t_i);
+ *   - p and q are the step's distributions (its temperatures); sequences with a target or draft temperature of 0
+ *     contribute nothing; with accepted_only != 0 only n-grams the target accepted count.
+ * Must be called after ot_verify_step / ot_verify_step_from_logits on this context with the same `in`, and with
+ * that step's output buffers: it reads the translation from them and the logits and row statistics from the
+ * context's workspace (`target_logits`: the pointer given to ot_verify_step_from_logits, or NULL after
+ * ot_verify_step).  Work is enqueued on the context's stream.                                                  */
+#define OT_LAMBDA_FIXED          0
+#define OT_LAMBDA_TARGET_PROB    1
+#define OT_NGRAM_TERM_NLL        0
+#define OT_NGRAM_TERM_APPROX_KL  1
+typedef struct ot_loss_config {
+  float   lambda;         /* used with OT_LAMBDA_FIXED (0.2 in the paper's experiments)                          */
+  int32_t lambda_mode;    /* OT_LAMBDA_*                                                                         */
+  int32_t ngram_term;     /* OT_NGRAM_TERM_*                                                                     */
+  int32_t accepted_only;  /* != 0: n-gram tokens at mapped positions j >= n_accept[b] are left out               */
+} ot_loss_config;
+/* Caller-allocated DEVICE buffers.  Per row ([M], entry row_off[b] + j is mapped token j of sequence b):
+ *   kind    0 no term, 1 direct-mapping token (KL term), 2 n-gram token
+ *   kl      the KL term of a direct-mapping token, or of an n-gram token with OT_NGRAM_TERM_APPROX_KL, else 0
+ *   nll     -sum ln q(d) over the sub-tokens of an n-gram token, else 0
+ *   weight  lambda of an n-gram token, else 0
+ *   totals  [5]: sum of the KL terms of direct-mapping tokens; sum of weight * (nll or kl) of n-gram tokens; number
+ *           of direct-mapping tokens; number of n-gram sub-tokens; loss = (sum 1 + sum 2) / max(1, count 1 + count 2)
+ *   qprime  optional (may be NULL): [M, V_t] fp32, row row_off[b] + j = q' of Eq. 2 over the whole target vocabulary
+ *           at mapped position j (with the overrides of the n-gram matched there), zeros for rows without a term   */
+typedef struct ot_loss_out {
+  int32_t* kind;
+  double  *kl, *nll, *weight, *totals;
+  float*   qprime;
+} ot_loss_out;
+int ot_distill_loss(ot_ctx* ctx, const ot_step_in* in, const ot_step_out* step_out, const float* target_logits_or_null,
+                    const ot_loss_config* cfg, ot_loss_out* out);
+
 /* ---- diagnostics ---------------------------------------------------------------------------------------- */
 /* Device pointers into the context's workspace, valid until ot_verify_destroy and overwritten by every step.
  * Row statistics are those of the softmax of the Notation paragraph: p_j(v) = exp((z_v - row_max)/T) / row_sumexp. */

@@ -24,12 +24,14 @@ OT_N_STAGES = 5
 STAGE_NAMES = ("lm_head", "softmax_stats", "translate_accept", "resid_sums", "resid_pick")
 
 OT_EVICT_NONE, OT_EVICT_LRU, OT_EVICT_LFU = 0, 1, 2
+OT_LAMBDA_FIXED, OT_LAMBDA_TARGET_PROB = 0, 1
+OT_NGRAM_TERM_NLL, OT_NGRAM_TERM_APPROX_KL = 0, 1
 
 EXPORTS = (
     "ot_verify_init", "ot_verify_destroy", "ot_ngram_cache_build", "ot_ngram_cache_create", "ot_ngram_cache_insert",
     "ot_ngram_cache_size", "ot_ngram_cache_export", "ot_ngram_cache_destroy", "ot_verify_step",
-    "ot_verify_step_from_logits", "ot_verify_workspace", "ot_verify_profile", "ot_verify_profile_read",
-    "ot_last_error", "ot_version",
+    "ot_verify_step_from_logits", "ot_distill_loss", "ot_verify_workspace", "ot_verify_profile",
+    "ot_verify_profile_read", "ot_last_error", "ot_version",
 )
 
 
@@ -64,6 +66,17 @@ OUT_F32_M = ("p_tok", "q_tok", "ratio")
 
 class ot_step_out(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in OUT_INT_B + OUT_INT_M + OUT_F32_M]
+
+
+class ot_loss_config(C.Structure):
+    _fields_ = [("lambda", C.c_float), ("lambda_mode", C.c_int32), ("ngram_term", C.c_int32), ("accepted_only", C.c_int32)]
+
+
+LOSS_OUT = ("kind", "kl", "nll", "weight", "totals", "qprime")
+
+
+class ot_loss_out(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in LOSS_OUT]
 
 
 class ot_workspace_view(C.Structure):
@@ -107,6 +120,9 @@ def load_library() -> C.CDLL:
     lib.ot_verify_step.restype = C.c_int
     lib.ot_verify_step_from_logits.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(ot_step_in), C.c_void_p, C.POINTER(ot_step_out)]
     lib.ot_verify_step_from_logits.restype = C.c_int
+    lib.ot_distill_loss.argtypes = [C.c_void_p, C.POINTER(ot_step_in), C.POINTER(ot_step_out), C.c_void_p,
+                                    C.POINTER(ot_loss_config), C.POINTER(ot_loss_out)]
+    lib.ot_distill_loss.restype = C.c_int
     lib.ot_verify_workspace.argtypes = [C.c_void_p, C.POINTER(ot_workspace_view)]
     lib.ot_verify_workspace.restype = C.c_int
     lib.ot_verify_profile.argtypes = [C.c_void_p, C.c_int32]
@@ -230,6 +246,15 @@ def ot_verify_step(ctx, cache, step_in: ot_step_in, step_out: ot_step_out):
 
 def ot_verify_step_from_logits(ctx, cache, step_in: ot_step_in, target_logits, step_out: ot_step_out):
     _check(load_library().ot_verify_step_from_logits(ctx, cache, C.byref(step_in), _ptr(target_logits), C.byref(step_out)))
+
+
+def ot_distill_loss(ctx, step_in: ot_step_in, step_out: ot_step_out, target_logits, *, lam: float, lambda_mode: int,
+                    ngram_term: int, accepted_only: bool, buffers: dict):
+    """buffers: name -> device tensor/address for the fields of ot_loss_out ("qprime" may be absent)."""
+    cfg = ot_loss_config(float(lam), int(lambda_mode), int(ngram_term), 1 if accepted_only else 0)
+    out = ot_loss_out(*[_ptr(buffers.get(n)) for n in LOSS_OUT])
+    _check(load_library().ot_distill_loss(ctx, C.byref(step_in), C.byref(step_out), _ptr(target_logits), C.byref(cfg),
+                                          C.byref(out)))
 
 
 def ot_verify_workspace(ctx) -> ot_workspace_view:

@@ -1,4 +1,4 @@
-// Host-side structures shared by the translation units that implement the C ABI (api.hip, cache.hip).
+// Host-side structures shared by the translation units that implement the C ABI (api.hip, cache.hip, loss.hip).
 #pragma once
 
 #include <vector>
@@ -27,6 +27,8 @@ struct ot_ctx {
   int32_t* fpart_arg = nullptr;
   double *tile_r = nullptr, *tile_p = nullptr;
   otv::FinalInfo* fin = nullptr;
+  void* loss_rows = nullptr;          // [max_rows] records of kLossRowBytes: per-token constants of the loss kernels
+  double* loss_tiles = nullptr;       // [max_rows, ntiles] KL tile sums
   // profiling
   bool profiling = false;
   std::vector<hipEvent_t> events;   // OT_N_STAGES + 1 per pending step

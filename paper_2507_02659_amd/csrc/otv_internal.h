@@ -14,6 +14,7 @@ constexpr int kStatChunk = 4096;     // logits per workgroup of the softmax-stat
 constexpr int kResidTile = 1024;     // vocabulary entries per workgroup of the residual kernel
 constexpr int kGemmColsPerWave = 64; // LM-head columns owned by one wavefront
 constexpr int kGemmKPad = 128;       // packed K extent is a multiple of this
+constexpr int kLossRowBytes = 128;   // size of the per-token record of the distillation-loss kernels
 
 inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 

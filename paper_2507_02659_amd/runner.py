@@ -129,6 +129,36 @@ class Verifier:
         else:
             ot.ot_verify_step(self.ctx, cache, sin, sout)
 
+    def distill_loss(self, inp: dict, *, from_logits: bool = False, lam: float = 0.2, lambda_mode: int = ot.OT_LAMBDA_FIXED,
+                     ngram_term: int = ot.OT_NGRAM_TERM_NLL, accepted_only: bool = False, with_qprime: bool = False,
+                     sync: bool = True) -> Optional[dict]:
+        """Enqueues ot_distill_loss after a step on `inp`; with sync, waits and returns its outputs as numpy arrays."""
+        dev = self.device
+        M = max(inp["M"], 1)
+        key = ("loss_buffers", M, with_qprime)
+        buf = inp.get(key)
+        if buf is None:
+            buf = {"kind": torch.full((M,), -7, dtype=torch.int32, device=dev),
+                   "totals": torch.full((5,), -7.0, dtype=torch.float64, device=dev)}
+            buf.update({n: torch.full((M,), -7.0, dtype=torch.float64, device=dev) for n in ("kl", "nll", "weight")})
+            if with_qprime:
+                buf["qprime"] = torch.full((M, self.V_t), -7.0, dtype=torch.float32, device=dev)
+            inp[key] = buf
+        sin = ot.make_step_in(B=inp["B"], step=inp["step"], row_off=inp["row_off"], row_off_host=inp["row_off_host"],
+                              hidden=inp["hidden"], draft_logits=inp["draft_logits"], draft_ids=inp["draft_ids"],
+                              temperature=inp["temperature"], draft_temperature=inp["draft_temperature"],
+                              seq_id=inp["seq_id"], seed=inp["seed"])
+        ot.ot_distill_loss(self.ctx, sin, ot.make_step_out(inp["out"]), inp["target_logits"] if from_logits else None,
+                           lam=lam, lambda_mode=lambda_mode, ngram_term=ngram_term, accepted_only=accepted_only, buffers=buf)
+        if not sync:
+            return None
+        self.synchronize()
+        res = {n: t.cpu().numpy()[:inp["M"]] for n, t in buf.items() if n != "totals"}
+        totals = buf["totals"].cpu().numpy()
+        res.update(loss_dm=float(totals[0]), loss_ngram=float(totals[1]), n_dm=int(totals[2]), n_ngram_tokens=int(totals[3]),
+                   loss=float(totals[4]))
+        return res
+
     def synchronize(self):
         if self.stream is not None:
             self.stream.synchronize()
