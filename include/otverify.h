@@ -208,6 +208,39 @@ typedef struct ot_loss_out {
 int ot_distill_loss(ot_ctx* ctx, const ot_step_in* in, const ot_step_out* step_out, const float* target_logits_or_null,
                     const ot_loss_config* cfg, ot_loss_out* out);
 
+/* ---- adaptive drafting: stop rule and the acceptance head's loss value -------------------------------- */
+/* Section "Online Adaptive Drafting": a head f_phi gives, for proposed token i, the logit of
+ * P(y_i accepted | y_<i accepted) = sigmoid(f_phi(e_i)); drafting exits once
+ * P(some y_i', i' <= i, rejected) = 1 - prod_{i' <= i} sigmoid(f_phi(e_i')) exceeds gamma.  The head is trained
+ * with a weighted binary cross-entropy against the labels min(1, p/q), which ot_verify_step outputs as `ratio`.
+ * The head's layers are the drafter's business: its logits are the input.  Arrays are laid out like the step's
+ * per-row outputs: entry row_off[b] + i belongs to proposed token i of sequence b (the last row of a sequence
+ * is unused).  Only the first n_valid[b] tokens of sequence b are considered (NULL: all k_b).
+ *   p_accept      sigmoid(head_logits), 0 for unused entries
+ *   p_any_reject  1 - running product of p_accept within the sequence
+ *   n_keep        [B] min{i >= 1 : p_any_reject at token i-1 > gamma}, the token that tips the rule is kept; or
+ *                 the number of tokens considered if the rule never fires
+ *   bce           optional (may be NULL, needs `labels`): [3] = sum over the tokens considered of
+ *                 -(w_accept * l * ln sigmoid(a) + w_reject * (1 - l) * ln(1 - sigmoid(a))), their number, the mean
+ * All buffers are DEVICE memory except row_off_host; work is enqueued on the context's stream.                 */
+typedef struct ot_adapt_in {
+  int32_t        B;
+  float          gamma;          /* stopping threshold (0.3 / 0.7 in the paper's experiments)                    */
+  float          w_accept, w_reject;
+  int32_t        reserved;       /* must be 0                                                                    */
+  const int32_t* row_off;        /* DEVICE [B+1]                                                                 */
+  const int32_t* row_off_host;   /* HOST   [B+1]                                                                 */
+  const float*   head_logits;    /* DEVICE [M] f_phi(e_i)                                                        */
+  const float*   labels;         /* DEVICE [M] acceptance ratios in [0, 1], or NULL                              */
+  const int32_t* n_valid;        /* DEVICE [B], or NULL                                                          */
+} ot_adapt_in;
+typedef struct ot_adapt_out {
+  float   *p_accept, *p_any_reject;   /* [M]                                                                     */
+  int32_t *n_keep;                    /* [B]                                                                     */
+  double  *bce;                       /* [3] or NULL                                                             */
+} ot_adapt_out;
+int ot_adaptive_drafting(ot_ctx* ctx, const ot_adapt_in* in, ot_adapt_out* out);
+
 /* ---- diagnostics ---------------------------------------------------------------------------------------- */
 /* Device pointers into the context's workspace, valid until ot_verify_destroy and overwritten by every step.
  * Row statistics are those of the softmax of the Notation paragraph: p_j(v) = exp((z_v - row_max)/T) / row_sumexp. */

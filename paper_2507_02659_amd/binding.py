@@ -30,7 +30,7 @@ OT_NGRAM_TERM_NLL, OT_NGRAM_TERM_APPROX_KL = 0, 1
 EXPORTS = (
     "ot_verify_init", "ot_verify_destroy", "ot_ngram_cache_build", "ot_ngram_cache_create", "ot_ngram_cache_insert",
     "ot_ngram_cache_size", "ot_ngram_cache_export", "ot_ngram_cache_destroy", "ot_verify_step",
-    "ot_verify_step_from_logits", "ot_distill_loss", "ot_verify_workspace", "ot_verify_profile",
+    "ot_verify_step_from_logits", "ot_distill_loss", "ot_adaptive_drafting", "ot_verify_workspace", "ot_verify_profile",
     "ot_verify_profile_read", "ot_last_error", "ot_version",
 )
 
@@ -79,6 +79,16 @@ class ot_loss_out(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in LOSS_OUT]
 
 
+class ot_adapt_in(C.Structure):
+    _fields_ = [("B", C.c_int32), ("gamma", C.c_float), ("w_accept", C.c_float), ("w_reject", C.c_float), ("reserved", C.c_int32),
+                ("row_off", C.c_void_p), ("row_off_host", C.c_void_p), ("head_logits", C.c_void_p), ("labels", C.c_void_p),
+                ("n_valid", C.c_void_p)]
+
+
+class ot_adapt_out(C.Structure):
+    _fields_ = [("p_accept", C.c_void_p), ("p_any_reject", C.c_void_p), ("n_keep", C.c_void_p), ("bce", C.c_void_p)]
+
+
 class ot_workspace_view(C.Structure):
     _fields_ = [
         ("logits", C.c_void_p), ("ld_logits", C.c_int64), ("row_max", C.c_void_p), ("row_sumexp", C.c_void_p),
@@ -123,6 +133,8 @@ def load_library() -> C.CDLL:
     lib.ot_distill_loss.argtypes = [C.c_void_p, C.POINTER(ot_step_in), C.POINTER(ot_step_out), C.c_void_p,
                                     C.POINTER(ot_loss_config), C.POINTER(ot_loss_out)]
     lib.ot_distill_loss.restype = C.c_int
+    lib.ot_adaptive_drafting.argtypes = [C.c_void_p, C.POINTER(ot_adapt_in), C.POINTER(ot_adapt_out)]
+    lib.ot_adaptive_drafting.restype = C.c_int
     lib.ot_verify_workspace.argtypes = [C.c_void_p, C.POINTER(ot_workspace_view)]
     lib.ot_verify_workspace.restype = C.c_int
     lib.ot_verify_profile.argtypes = [C.c_void_p, C.c_int32]
@@ -255,6 +267,14 @@ def ot_distill_loss(ctx, step_in: ot_step_in, step_out: ot_step_out, target_logi
     out = ot_loss_out(*[_ptr(buffers.get(n)) for n in LOSS_OUT])
     _check(load_library().ot_distill_loss(ctx, C.byref(step_in), C.byref(step_out), _ptr(target_logits), C.byref(cfg),
                                           C.byref(out)))
+
+
+def ot_adaptive_drafting(ctx, *, B, gamma, w_accept=1.0, w_reject=1.0, row_off, row_off_host, head_logits, labels=None,
+                         n_valid=None, p_accept, p_any_reject, n_keep, bce=None, reserved=0):
+    ain = ot_adapt_in(int(B), float(gamma), float(w_accept), float(w_reject), int(reserved), _ptr(row_off), _ptr(row_off_host),
+                      _ptr(head_logits), _ptr(labels), _ptr(n_valid))
+    aout = ot_adapt_out(_ptr(p_accept), _ptr(p_any_reject), _ptr(n_keep), _ptr(bce))
+    _check(load_library().ot_adaptive_drafting(ctx, C.byref(ain), C.byref(aout)))
 
 
 def ot_verify_workspace(ctx) -> ot_workspace_view:

@@ -16,7 +16,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OUT_DIR = os.path.join(PKG, "_build")
 LIB_PATH = os.path.join(PKG, "libotverify.so")
-SOURCES = ["api.hip", "cache.hip", "lmhead.hip", "stats.hip", "accept.hip", "resid.hip", "loss.hip"]
+SOURCES = ["api.hip", "cache.hip", "lmhead.hip", "stats.hip", "accept.hip", "resid.hip", "loss.hip", "adapt.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -124,6 +124,7 @@ int ot_verify_init(const ot_verify_config* cfg, ot_ctx** out) {
     ok = ok && dev_alloc(c, &rows, R * kLossRowBytes) && dev_alloc(c, &c->loss_tiles, R * c->ntiles);
     c->loss_rows = rows;
   }
+  ok = ok && dev_alloc(c, &c->adapt_part, 2 * Bm);
   ok = ok && dev_alloc(c, &c->tile_r, Bm * c->ntiles) && dev_alloc(c, &c->tile_p, Bm * c->ntiles);
   if (!ok) { free_ctx(c); return fail(OT_ERR_NOMEM, "ot_verify_init: device allocation failed"); }
 

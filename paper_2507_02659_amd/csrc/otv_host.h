@@ -1,4 +1,4 @@
-// Host-side structures shared by the translation units that implement the C ABI (api.hip, cache.hip, loss.hip).
+// Host-side structures shared by the translation units that implement the C ABI (api.hip, cache.hip, loss.hip, adapt.hip).
 #pragma once
 
 #include <vector>
@@ -29,6 +29,7 @@ struct ot_ctx {
   otv::FinalInfo* fin = nullptr;
   void* loss_rows = nullptr;          // [max_rows] records of kLossRowBytes: per-token constants of the loss kernels
   double* loss_tiles = nullptr;       // [max_rows, ntiles] KL tile sums
+  double* adapt_part = nullptr;       // [max_batch, 2] per-sequence partials of the acceptance head's loss
   // profiling
   bool profiling = false;
   std::vector<hipEvent_t> events;   // OT_N_STAGES + 1 per pending step

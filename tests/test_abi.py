@@ -42,12 +42,14 @@ def test_struct_layouts_match_the_header():
             out += [n.strip().lstrip("*") for n in names.split(",")]
         return out
 
-    for cls in (ot.ot_verify_config, ot.ot_step_in, ot.ot_step_out, ot.ot_workspace_view, ot.ot_loss_config, ot.ot_loss_out):
+    for cls in (ot.ot_verify_config, ot.ot_step_in, ot.ot_step_out, ot.ot_workspace_view, ot.ot_loss_config, ot.ot_loss_out,
+                ot.ot_adapt_in, ot.ot_adapt_out):
         assert [f[0] for f in cls._fields_] == fields(cls.__name__), cls.__name__
     assert C.sizeof(ot.ot_verify_config) == 8 * 4 + 3 * 8
     assert C.sizeof(ot.ot_step_in) == 8 + 8 * 8 + 8
     assert C.sizeof(ot.ot_step_out) == 14 * 8
     assert C.sizeof(ot.ot_loss_config) == 16 and C.sizeof(ot.ot_loss_out) == 6 * 8
+    assert C.sizeof(ot.ot_adapt_in) == 24 + 5 * 8 and C.sizeof(ot.ot_adapt_out) == 4 * 8
 
 
 def test_init_argument_errors_need_no_gpu():
