@@ -121,8 +121,7 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
   __shared__ int32_t sRowOff[kFusedMaxB + 1];
   __shared__ float sTemp[kFusedMaxB + 1];
   __shared__ float sScale[MT * 16];
-  static_assert(WPG * MT * 64 * 8 <= MT * 16 * KC * 2, "the per-lane row statistics reuse the two hidden buffers");
-  static_assert(WPG * 64 >= MT * 16 && WPG * 64 >= kFusedMaxB + 1, "one thread per row / per sequence");
+  static_assert(WPG * 64 >= kFusedMaxB + 1, "one thread per sequence stages its row offset and temperature");
   static_assert((WPG & (WPG - 1)) == 0, "the mask below tells the compiler the range of the wavefront index");
   const int tid = threadIdx.x, wave = (tid >> 6) & (WPG - 1), lane = tid & 63;
   // Workgroup id -> (column tile, M-block).  Consecutive ids go round-robin to the 8 XCDs, each with its own L2; the
@@ -147,8 +146,8 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
     for (int nw = 0; nw < NW; ++nw) acc[mt][nw] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   // Swizzle key of a row: the 16-byte chunks of a row are XORed with it.  Rows of 256 bytes: the row index; rows of
-  // 128 bytes: rows r and r+8 would meet in the same banks, so bit 3 is folded into bit 0.
-  auto row_key = [](int row) { return kCPR == 16 ? (row & 15) : ((row ^ (row >> 3)) & 7); };
+  // 128 bytes: rows r and r+8 of a 16-row tile would meet in the same banks, so bit 3 is folded into bit 0.
+  auto row_key = [](int row) { return kCPR == 16 ? (row & 15) : ((row ^ ((row & 15) >> 3)) & 7); };
   // request slice kc (in 32-column steps) into buffer s: chunk q of the buffer holds logical chunk (q%kCPR)^key(row).
   // A request past the end of K re-reads the last slice, so that every slice issues the same number of loads and
   // the in-order load counter can be waited on by number.
@@ -254,18 +253,22 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
     // and sum exp((z - max)/T), first per wavefront (NW*16 columns), then merged over the wavefronts; one partial per
     // row and column tile goes to memory.  All LDS buffers of the main loop are free: every wavefront has passed the
     // barrier that followed its last slice (the weight ring may still receive the surplus refills; it is not used).
+    // The statistics scratch (3 x 4 bytes per lane and row tile) reuses the two hidden buffers; when those are too
+    // small for all row tiles at once the row tiles are taken in groups of kStatMT.
+    constexpr int kStatMT = MT * KC / (16 * WPG) < MT ? MT * KC / (16 * WPG) : MT;
+    static_assert(kStatMT >= 1 && MT % kStatMT == 0, "row tiles split evenly into statistics groups");
     float* st_max = reinterpret_cast<float*>(sA);
-    float* st_sum = st_max + WPG * MT * 64;
+    float* st_sum = st_max + WPG * kStatMT * 64;
     int32_t* st_arg = reinterpret_cast<int32_t*>(sB);
-    if (tid < MT * 16) {
-      const int row = min(row0 + tid, M - 1);
+    for (int r = tid; r < MT * 16; r += WPG * 64) {
+      const int row = min(row0 + r, M - 1);
       int lo = 0, hi = fs.B - 1;                    // sequence that owns the row: last b with row_off[b] <= row
       while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
         if (sRowOff[mid] <= row) lo = mid; else hi = mid - 1;
       }
       const float T_b = sTemp[lo];
-      sScale[tid] = T_b > 0.f ? 1.4426950408889634f / T_b : 1.4426950408889634f;
+      sScale[r] = T_b > 0.f ? 1.4426950408889634f / T_b : 1.4426950408889634f;
     }
     lds_barrier();
     // every lane reduces its own NW*4 values of a row (no cross-lane traffic) and parks the partial in LDS; only a
@@ -273,53 +276,58 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
     const int n_valid = active ? V_t - (t16 * 16 + 4 * (lane >> 4)) : 0;   // this lane's columns n0 + 16*nw + e < V_t
     const bool all_valid = __builtin_amdgcn_readfirstlane(active && (t16 + NW) * 16 <= V_t);
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const float sc = sScale[mt * 16 + (lane & 15)];
-      float v[NW * 4];
+    for (int h = 0; h < MT; h += kStatMT) {
 #pragma unroll
-      for (int nw = 0; nw < NW; ++nw)
+      for (int ml = 0; ml < kStatMT; ++ml) {
+        const int mt = h + ml;
+        const float sc = sScale[mt * 16 + (lane & 15)];
+        float v[NW * 4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-          v[nw * 4 + e] = (all_valid || nw * 16 + e < n_valid) ? acc[mt][nw][e] : -INFINITY;
-      float best = v[0];
-      int bi = 0;
+        for (int nw = 0; nw < NW; ++nw)
 #pragma unroll
-      for (int i = 1; i < NW * 4; ++i)              // ascending columns: the first maximum is kept
-        if (v[i] > best) { best = v[i]; bi = i; }
-      const int barg = best == -INFINITY ? 0x7FFFFFFF : t16 * 16 + 4 * (lane >> 4) + (bi >> 2) * 16 + (bi & 3);
-      const float nb = best == -INFINITY ? 0.f : -best * sc;
-      float sum = 0.f;
+          for (int e = 0; e < 4; ++e)
+            v[nw * 4 + e] = (all_valid || nw * 16 + e < n_valid) ? acc[mt][nw][e] : -INFINITY;
+        float best = v[0];
+        int bi = 0;
 #pragma unroll
-      for (int i = 0; i < NW * 4; ++i) sum += __builtin_amdgcn_exp2f(fmaf(v[i], sc, nb));   // masked: exp2(-inf) = 0
-      const int at = (wave * (MT * 16) + mt * 16 + (lane & 15)) * 4 + (lane >> 4);
-      st_max[at] = best; st_sum[at] = sum; st_arg[at] = barg;
-    }
-    lds_barrier();
-    // one thread per row merges the WPG x 4 partials in a fixed order and writes the tile's partial
-    if (tid < MT * 16 && row0 + tid < M) {
-      const float sc = sScale[tid];
-      float best = -INFINITY;
-      int barg = 0x7FFFFFFF;
+        for (int i = 1; i < NW * 4; ++i)            // ascending columns: the first maximum is kept
+          if (v[i] > best) { best = v[i]; bi = i; }
+        const int barg = best == -INFINITY ? 0x7FFFFFFF : t16 * 16 + 4 * (lane >> 4) + (bi >> 2) * 16 + (bi & 3);
+        const float nb = best == -INFINITY ? 0.f : -best * sc;
+        float sum = 0.f;
 #pragma unroll
-      for (int w = 0; w < WPG; ++w) {
-        const f32x4 m4 = *reinterpret_cast<const f32x4*>(&st_max[(w * (MT * 16) + tid) * 4]);
-        const int4 a4 = *reinterpret_cast<const int4*>(&st_arg[(w * (MT * 16) + tid) * 4]);
-        const int a[4] = {a4.x, a4.y, a4.z, a4.w};
-#pragma unroll
-        for (int g = 0; g < 4; ++g)
-          if (m4[g] > best || (m4[g] == best && a[g] < barg)) { best = m4[g]; barg = a[g]; }
+        for (int i = 0; i < NW * 4; ++i) sum += __builtin_amdgcn_exp2f(fmaf(v[i], sc, nb));   // masked: exp2(-inf) = 0
+        const int at = (wave * (kStatMT * 16) + ml * 16 + (lane & 15)) * 4 + (lane >> 4);
+        st_max[at] = best; st_sum[at] = sum; st_arg[at] = barg;
       }
-      float sum = 0.f;
+      lds_barrier();
+      // one thread per row merges the WPG x 4 partials in a fixed order and writes the tile's partial
+      if (tid < kStatMT * 16 && row0 + h * 16 + tid < M) {
+        const float sc = sScale[h * 16 + tid];
+        float best = -INFINITY;
+        int barg = 0x7FFFFFFF;
 #pragma unroll
-      for (int w = 0; w < WPG; ++w) {
-        const f32x4 m4 = *reinterpret_cast<const f32x4*>(&st_max[(w * (MT * 16) + tid) * 4]);
-        const f32x4 s4 = *reinterpret_cast<const f32x4*>(&st_sum[(w * (MT * 16) + tid) * 4]);
+        for (int w = 0; w < WPG; ++w) {
+          const f32x4 m4 = *reinterpret_cast<const f32x4*>(&st_max[(w * (kStatMT * 16) + tid) * 4]);
+          const int4 a4 = *reinterpret_cast<const int4*>(&st_arg[(w * (kStatMT * 16) + tid) * 4]);
+          const int a[4] = {a4.x, a4.y, a4.z, a4.w};
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
-          if (m4[g] != -INFINITY) sum += s4[g] * __builtin_amdgcn_exp2f((m4[g] - best) * sc);
+          for (int g = 0; g < 4; ++g)
+            if (m4[g] > best || (m4[g] == best && a[g] < barg)) { best = m4[g]; barg = a[g]; }
+        }
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < WPG; ++w) {
+          const f32x4 m4 = *reinterpret_cast<const f32x4*>(&st_max[(w * (kStatMT * 16) + tid) * 4]);
+          const f32x4 s4 = *reinterpret_cast<const f32x4*>(&st_sum[(w * (kStatMT * 16) + tid) * 4]);
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+            if (m4[g] != -INFINITY) sum += s4[g] * __builtin_amdgcn_exp2f((m4[g] - best) * sc);
+        }
+        const int64_t o = (int64_t)(row0 + h * 16 + tid) * fs.nfine + col_tile;
+        fs.fmax[o] = best; fs.fsum[o] = sum; fs.farg[o] = barg;
       }
-      const int64_t o = (int64_t)(row0 + tid) * fs.nfine + col_tile;
-      fs.fmax[o] = best; fs.fsum[o] = sum; fs.farg[o] = barg;
+      if (h + kStatMT < MT) lds_barrier();         // the next group overwrites the scratch
     }
   }
   if (!active) return;
@@ -487,7 +495,11 @@ hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* W
   if (tiles <= 2) return launch_wide<2, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
   if (tiles <= 4) return launch_wide<4, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
   if (tiles <= 6) return launch_wide<6, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
-  // 144 rows per M-block; more rows run as several M-blocks per column tile (their weight streams meet in one L2)
+  // More than 144 rows run as several M-blocks per column tile; their weight streams meet in one L2.  A workgroup
+  // moves 2 MB of weights and 8 KB of hidden state per row through LDS, and that L2 -> LDS traffic bounds this
+  // regime, so M-blocks of 288 rows (hidden slices of 64 columns, weight ring two steps deep) are 4-8 % faster per
+  // row than blocks of 144; they are used when they add no padding (the last block is more than half full).
+  if (ceil_div(M, 288) * 2 == ceil_div(M, 144)) return launch_wide<18, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
   return launch_wide<9, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
 }
 
