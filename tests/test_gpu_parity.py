@@ -218,6 +218,22 @@ def test_more_sequences_than_the_lm_head_stages():
     _run_and_compare(make_case(spec), max_divergent=4)
 
 
+@pytest.mark.parametrize("M,B", [(16, 2), (17, 2), (33, 3), (96, 6), (97, 6), (144, 9), (145, 9), (288, 12), (289, 12), (300, 255),
+                                 (300, 256), (433, 20)])
+def test_row_count_boundaries_end_to_end(M, B):
+    """Whole steps from hidden states at the row counts where the LM head changes kernel, M-block size or the number of
+    M-blocks, and at the sequence count where its epilogue stops emitting the row statistics."""
+    ks = [M // B - 1] * B
+    for i in range(M - sum(k + 1 for k in ks)):
+        ks[i] += 1
+    temps = [[1.0, 0.6, 0.0, 1.4][i % 4] for i in range(B)]
+    spec = CaseSpec(name=f"rows_{M}_{B}", dtype="bf16", d=64, V_t=1111, V_d=500, k=ks, temperature=temps, n_direct=400,
+                    n_ngram=150, ngram_len=(2, 4), plant_cover=0.4, align=0.8, data_seed=1000 + M + B, philox_seed=9)
+    case = make_case(spec)
+    assert case.M == M and case.B == B
+    _run_and_compare(case, max_divergent=max(2, B // 8))
+
+
 def test_draft_temperature_variants():
     spec = CaseSpec(name="edge_td", dtype="f32", d=64, V_t=2500, V_d=1000, k=[5] * 12, temperature=[1.0] * 6 + [0.0] * 6,
                     draft_temperature=[0.0, 0.5, 2.0] * 4, n_direct=800, n_ngram=200, ngram_len=(2, 3), plant_cover=0.3,
