@@ -122,14 +122,8 @@ __global__ __launch_bounds__(kThreads) void loss_kl_tiles_kernel(LossArgs a) {
   const int row = blockIdx.y, tile = blockIdx.x, tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int first = tile * kResidTile + tid;
-  int dv[kPer];
-#pragma unroll
-  for (int e = 0; e < kPer; ++e) {                       // independent of the row's constants: issued first
-    const int v = first + e * kThreads;
-    dv[e] = v < a.V_t ? a.tmap[v] : -1;
-  }
   const LossRow R = a.rows[row];
-  if (!R.need_tiles) {
+  if (!R.need_tiles) {                                   // most rows of a batch: checked before anything is fetched
     if (a.out.qprime) {                                  // rows without a token export zeros
 #pragma unroll
       for (int e = 0; e < kPer; ++e) {
@@ -140,13 +134,16 @@ __global__ __launch_bounds__(kThreads) void loss_kl_tiles_kernel(LossArgs a) {
     return;
   }
   const float* z = a.Z + (int64_t)row * a.ldz;
+  int dv[kPer];
   float zv[kPer], xq[kPer];
 #pragma unroll
   for (int e = 0; e < kPer; ++e) {
     const int v = first + e * kThreads;
+    dv[e] = v < a.V_t ? a.tmap[v] : -1;
     zv[e] = v < a.V_t ? z[v] : 0.f;
-    xq[e] = dv[e] >= 0 ? draft_logit(a, R.drow, dv[e]) : 0.f;
   }
+#pragma unroll
+  for (int e = 0; e < kPer; ++e) xq[e] = dv[e] >= 0 ? draft_logit(a, R.drow, dv[e]) : 0.f;
   double term[kPer];
 #pragma unroll
   for (int e = 0; e < kPer; ++e) {
