@@ -234,6 +234,29 @@ def test_row_count_boundaries_end_to_end(M, B):
     _run_and_compare(case, max_divergent=max(2, B // 8))
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes_end_to_end(seed):
+    """Seeded random batch shapes, vocabulary sizes, temperatures, cache settings and dtypes through the whole step."""
+    rng = np.random.default_rng(7000 + seed)
+    B = int(rng.integers(1, 41))
+    kmax = int(rng.choice([3, 8, 20, 63]))
+    k = rng.integers(0, kmax + 1, size=B).tolist()
+    if seed % 6 == 0:
+        k[0] = 63
+    V_d = int(rng.integers(100, 3000))
+    V_t = int(rng.integers(max(200, V_d // 2), 6000))
+    n_direct = int(rng.integers(V_d // 3, min(V_d, V_t - 60) + 1))
+    lmax = int(rng.integers(2, 9))
+    n_ngram = int(rng.choice([0, 40, min(500, V_t - n_direct - 10)]))
+    temps = rng.choice([0.0, 0.5, 1.0, 2.0], size=B, p=[0.15, 0.25, 0.45, 0.15]).tolist()
+    draft_t = None if seed % 3 else rng.choice([0.0, 0.7, 1.0], size=B, p=[0.2, 0.4, 0.4]).tolist()
+    spec = CaseSpec(name=f"rand_{seed}", dtype=str(rng.choice(["bf16", "f32"])), d=int(rng.integers(4, 21)) * 8, V_t=V_t, V_d=V_d, k=k,
+                    temperature=temps, draft_temperature=draft_t, n_direct=n_direct, n_ngram=n_ngram, ngram_len=(2, lmax),
+                    plant_cover=float(rng.choice([0.0, 0.3, 0.7])), align=float(rng.choice([0.0, 0.6, 0.9])), data_seed=9000 + seed,
+                    philox_seed=seed, logits_only=bool(rng.integers(0, 2)))
+    _run_and_compare(make_case(spec), max_divergent=max(2, B // 8))
+
+
 def test_draft_temperature_variants():
     spec = CaseSpec(name="edge_td", dtype="f32", d=64, V_t=2500, V_d=1000, k=[5] * 12, temperature=[1.0] * 6 + [0.0] * 6,
                     draft_temperature=[0.0, 0.5, 2.0] * 4, n_direct=800, n_ngram=200, ngram_len=(2, 3), plant_cover=0.3,
