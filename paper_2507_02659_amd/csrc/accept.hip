@@ -3,10 +3,10 @@
 //
 // Translation.  The draft rows' softmax partials are merged by 4 threads per row, thread i then forms
 // log q_i(d_i); every window (start s, length L) of the drafted ids is probed in the n-gram table by its own thread;
-// thread 0 walks the window left to right over LDS only: the longest cache hit at s yields one target token whose
-// log q' is the sum of the L sub-token log-probabilities (the product of Eq. 1, kept in log space so that five or
-// six factors of 1e-6 do not underflow), otherwise the direct image of d_s, and a draft id with neither ends the
-// proposal.
+// lane s prepares the segment that would start at s and the window is then walked left to right as a chase
+// through start + length: the longest cache hit at s yields one target token whose log q' is the sum of the L
+// sub-token log-probabilities (the product of Eq. 1, kept in log space so that five or six factors of 1e-6 do not
+// underflow), otherwise the direct image of d_s, and a draft id with neither ends the proposal.
 //
 // Acceptance.  The target rows' partials are merged the same way.  Lane j of the first wavefront owns mapped
 // position j: it forms p_j(t_j), the ratio min(1, p/q') and its Philox uniform; acceptance tests at different
@@ -100,13 +100,12 @@ __global__ __launch_bounds__(768) void translate_accept_kernel(StepArgs a) {
   const int q0 = r0 - b;
   __shared__ int32_t s_dm[64];
   __shared__ unsigned long long s_hit[64];   // (length << 60) | (slot << 32) | target of the longest cache hit starting here, 0 = none
-  __shared__ int32_t s_tok[64], s_start[64], s_len[64];
-  __shared__ double s_logq[64], s_lq[64];
+  __shared__ double s_logq[64];
   __shared__ float s_zq[64];
   __shared__ float s_qmx[64], s_pmx[64];
   __shared__ double s_qS[64], s_pS[64];
   __shared__ int s_qarg[64], s_parg[64];
-  __shared__ int s_bad, s_m, s_flags, s_send;
+  __shared__ int s_bad;
 
   // ---- loads that depend on nothing but b
   const float T = a.temperature[b];
@@ -116,7 +115,7 @@ __global__ __launch_bounds__(768) void translate_accept_kernel(StepArgs a) {
   const double invTd = Td > 0.f ? 1.0 / (double)Td : 1.0;
 
   if (tid == 0) s_bad = 0;
-  if (tid < 64) { s_hit[tid] = 0ull; s_tok[tid] = -1; s_start[tid] = -1; s_len[tid] = 0; s_lq[tid] = 0.0; s_dm[tid] = -1; }
+  if (tid < 64) { s_hit[tid] = 0ull; s_dm[tid] = -1; }
   __syncthreads();
   if (role == 0) {
     merge_partials(a.tpart_max, a.tpart_sum, a.tpart_arg, a.ncht, r0, k + 1, invT, s_pmx, s_pS, s_parg, a.row_max,
@@ -192,49 +191,58 @@ __global__ __launch_bounds__(768) void translate_accept_kernel(StepArgs a) {
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 
-  // ---- greedy left-to-right walk over LDS
-  if (tid == 0) {
-    int s = 0, j = 0, hits = 0, flags = 0;
-    while (s < k) {
-      int L, t;
-      if (s_hit[s] != 0ull) {
-        L = (int)(s_hit[s] >> 60); t = (int)(s_hit[s] & 0xFFFFFFFFull); ++hits;
-        // use statistics of the entry (Appendix, cache eviction): one more use, last used now
-        const unsigned int slot = (unsigned int)(s_hit[s] >> 32) & 0x0FFFFFFFu;
-        atomicAdd(&a.cache.uses[slot], 1u);
-        a.cache.last_used[slot] = a.cache.clock;
-      } else {
-        t = s_dm[s];
-        L = 1;
-        if (t < 0) { flags |= OT_FLAG_UNMAPPABLE; break; }
-      }
-      double lq = 0.0;
-      for (int l = 0; l < L; ++l) lq += s_logq[s + l];
-      s_tok[j] = t; s_start[j] = s; s_len[j] = L; s_lq[j] = lq;
-      s += L;
-      ++j;
+  // ---- greedy left-to-right walk.  Lane s first prepares the segment that would start at draft position s (the
+  // longest cache hit there, else the direct image; log q' = sum of its sub-tokens' log-probabilities); the walk
+  // itself is then a chase through "start + length" with wavefront-uniform lane reads, a few cycles per token.
+  const int lane = tid;
+  int seg_t = -1, seg_L = 1, seg_slot = -1;
+  double seg_lq = 0.0;
+  if (lane < k) {
+    const unsigned long long h = s_hit[lane];
+    if (h != 0ull) {
+      seg_L = (int)(h >> 60); seg_t = (int)(h & 0xFFFFFFFFull); seg_slot = (int)((h >> 32) & 0x0FFFFFFFull);
+    } else {
+      seg_t = s_dm[lane];
     }
-    s_m = j; s_flags = flags; s_send = s;
-    a.out.n_mapped[b] = j;
+    for (int l = 0; l < seg_L; ++l) seg_lq += s_logq[lane + l];
+  }
+  int m = 0, s_end = 0, flags = 0, start_j = -1;
+  while (s_end < k) {
+    const int at = __builtin_amdgcn_readfirstlane(s_end);
+    if (__builtin_amdgcn_readlane(seg_t, at) < 0) { flags |= OT_FLAG_UNMAPPABLE; break; }   // neither a hit nor a direct image
+    if (lane == m) start_j = at;
+    s_end = at + __builtin_amdgcn_readlane(seg_L, at);
+    ++m;
+  }
+  // lane j < m takes over the segment that starts at start_j
+  // (all lanes take part in the shuffles: a lane outside the active set would not supply its value)
+  const int src = start_j >= 0 ? start_j : 0;
+  const int got_t = __shfl(seg_t, src), got_L = __shfl(seg_L, src);
+  const double lq_j = __shfl(seg_lq, src);
+  const int slot_j = __shfl(seg_slot, src);
+  const int t_j = lane < m ? got_t : -1;
+  const int L_j = lane < m ? got_L : 0;
+  const int hits = __popcll(__ballot(lane < m && L_j > 1));
+  if (lane < m && L_j > 1) {
+    // use statistics of the entry (Appendix, cache eviction): one more use, last used now
+    atomicAdd(&a.cache.uses[slot_j], 1u);
+    a.cache.last_used[slot_j] = a.cache.clock;
+  }
+  if (lane == 0) {
+    a.out.n_mapped[b] = m;
     a.out.hits_proposed[b] = hits;
     a.out.flags[b] = flags;
   }
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 
   // ---- acceptance test of mapped position `lane` (first wavefront only)
-  const int lane = tid;
-  const int m = s_m, flags = s_flags;
   const uint32_t k0 = (uint32_t)a.seed, k1 = (uint32_t)(a.seed >> 32);
   const float mx = lane <= k ? s_pmx[lane] : 0.f;
   const double S = lane <= k ? s_pS[lane] : 1.0;
   const int arg = lane <= k ? s_parg[lane] : 0;
   bool ok = true;               // lanes >= m do not veto
-  const int t_j = s_tok[lane], L_j = s_len[lane], start_j = s_start[lane];
   double pt = 0.0, qp = 0.0, ratio = 0.0;
   if (lane < m) {
-    qp = exp(s_lq[lane]);
+    qp = exp(lq_j);
     if (T > 0.f) {
       const double z = (double)a.Z[(int64_t)(r0 + lane) * a.ldz + t_j];
       pt = exp((z - (double)mx) * invT) / S;
@@ -289,7 +297,7 @@ __global__ __launch_bounds__(768) void translate_accept_kernel(StepArgs a) {
         fin.mode = 2;                                   // everything accepted: free token ~ p
       } else {
         fin.mode = 3;                                   // correction token ~ norm(max(0, p - q'))
-        const int s = (n < m) ? fin_span_s : s_send;
+        const int s = (n < m) ? fin_span_s : s_end;
         fin.drow = q0 + s;
         fin.greedy_draft = !(Td > 0.f);
         fin.invTd = invTd;
