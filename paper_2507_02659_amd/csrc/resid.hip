@@ -134,54 +134,43 @@ __global__ __launch_bounds__(kThreads) void resid_pick_kernel(StepArgs a) {
   }
   __syncthreads();
   if (wave == 0) {
-    // Running mass over the tiles in ascending order: wavefront scan of 64 tiles at a time plus a carry.  The
-    // same routine gives the total (first call) and the crossing (second call), so both see identical sums.
-    auto scan = [&](const double* m, double target, bool search, int* pick, double* base) -> double {
+    // Running mass over the tiles in ascending order, in place: wavefront scan of 64 tiles at a time plus a carry.
+    // The total and the crossing both come from these same sums.
+    auto prefix = [&](double* m) -> double {
       double carry = 0.0;
-      *pick = -1;
       for (int t0 = 0; t0 < a.ntiles; t0 += 64) {
         const int t = t0 + lane;
-        const double x = t < a.ntiles ? m[t] : 0.0;
-        double incl = x;
+        double incl = t < a.ntiles ? m[t] : 0.0;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
           const double up = __shfl_up(incl, off);
           if (lane >= off) incl += up;
         }
         incl += carry;
-        double prev = __shfl_up(incl, 1);
-        if (lane == 0) prev = carry;
-        if (search) {
-          const unsigned long long hit = __ballot(t < a.ntiles && incl > target);
-          if (hit) {
-            const int l = (int)__ffsll((long long)hit) - 1;
-            *pick = t0 + l;
-            *base = __shfl(prev, l);
-            return carry;
-          }
-        }
+        if (t < a.ntiles) m[t] = incl;
         carry = __shfl(incl, 63);
       }
       return carry;
     };
-    int pick;
-    double base = 0.0;
-    const double* m = s_tiles;
-    double total = scan(m, 0.0, false, &pick, &base);
+    double* m = s_tiles;
+    double total = prefix(m);
     const int fallback = !(total > 0.0);    // residual of zero mass: draw from p
     if (fallback) {
       m = s_tiles + a.ntiles;
-      total = scan(m, 0.0, false, &pick, &base);
+      total = prefix(m);
     }
     const double target = f.u2 * total;
-    scan(m, target, true, &pick, &base);
-    if (pick < 0) {                          // rounding pushed the target past the end: take the last non-empty tile
-      int last_nz = 0;
-      for (int t = 0; t < a.ntiles; ++t) if (m[t] > 0.0) last_nz = t;
-      double below = 0.0;
-      for (int t = 0; t < last_nz; ++t) below += m[t];
-      pick = last_nz; base = below;
+    int pick = -1;
+    for (int t0 = 0; t0 < a.ntiles && pick < 0; t0 += 64) {
+      const int t = t0 + lane;
+      const unsigned long long hit = __ballot(t < a.ntiles && m[t] > target);
+      if (hit) pick = t0 + (int)__ffsll((long long)hit) - 1;
     }
+    if (pick < 0) {                          // rounding pushed the target past the end: take the last tile that adds mass
+      pick = 0;
+      for (int t = 1; t < a.ntiles; ++t) if (m[t] > m[t - 1]) pick = t;
+    }
+    const double base = pick > 0 ? m[pick - 1] : 0.0;
     if (lane == 0) {
       if (fallback) a.out.flags[b] |= OT_FLAG_RESID_ZERO;
       s_pick = pick; s_base = base; s_target = target; s_fallback = fallback;
