@@ -495,12 +495,26 @@ hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* W
   if (tiles <= 2) return launch_wide<2, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
   if (tiles <= 4) return launch_wide<4, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
   if (tiles <= 6) return launch_wide<6, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
-  // More than 144 rows run as several M-blocks per column tile; their weight streams meet in one L2.  A workgroup
-  // moves 2 MB of weights and 8 KB of hidden state per row through LDS, and that L2 -> LDS traffic bounds this
-  // regime, so M-blocks of 288 rows (hidden slices of 64 columns, weight ring two steps deep) are 4-8 % faster per
-  // row than blocks of 144; they are used when they add no padding (the last block is more than half full).
-  if (ceil_div(M, 288) * 2 == ceil_div(M, 144)) return launch_wide<18, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
-  return launch_wide<9, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
+  if (tiles <= 9) return launch_wide<9, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
+  // More than 144 rows run as several M-blocks per column tile; their weight streams meet in one L2.  This regime is
+  // bound by the L2 -> LDS traffic and by LDS reads, and the time of an M-block was measured to grow almost in
+  // proportion to its height (about 1.3 row tiles of fixed cost per block: 144, 256, 288 rows take 150, 251, 284 us at
+  // d = 4096, V_t = 128256), so the height that minimises blocks x (1.3 + row tiles) is taken: mostly the one that pads
+  // least.  Heights above 144 rows use hidden slices of 64 columns and a weight ring two steps deep to fit in LDS.
+  int best_mt = 9;
+  int best_cost = ceil_div(M, 144) * (13 + 10 * 9);
+  for (int mt : {10, 12, 14, 16, 18}) {
+    const int cost = ceil_div(M, 16 * mt) * (13 + 10 * mt);
+    if (cost <= best_cost) { best_cost = cost; best_mt = mt; }
+  }
+  switch (best_mt) {
+    case 10: return launch_wide<10, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
+    case 12: return launch_wide<12, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
+    case 14: return launch_wide<14, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
+    case 16: return launch_wide<16, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
+    case 18: return launch_wide<18, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
+    default: return launch_wide<9, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
+  }
 }
 
 hipError_t launch_lmhead_f32(const float* H, int M, int d, const float* W, float* Z, int V_t, int64_t ldz,
