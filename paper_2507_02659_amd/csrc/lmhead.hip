@@ -8,11 +8,15 @@
 //     fragments of 64 adjacent columns per 32-deep step are adjacent.  A wavefront streams the fragments of its
 //     columns with fully coalesced 1 KB loads: no transpose anywhere.
 //   * Every weight is used by exactly one wavefront, which keeps accumulators for ALL rows of the M-block
-//     (up to 9 x 16 rows), so W never has to be re-read for another row tile.
+//     (up to 9 x 16 rows while the product is bound by HBM), so W is read from HBM once.  More than 144 rows run as
+//     several M-blocks of up to 18 x 16 rows per column tile, scheduled so that they share W in one L2.
 //   * From 17 rows on, both operands travel by direct global->LDS loads.  The hidden rows, shared by the wavefronts
-//     of a workgroup, go through 128-deep double-buffered slices (swizzled rows: conflict-free 16-byte reads); each
-//     hidden fragment read from LDS feeds NW MFMAs.  The weight fragments go through a wavefront-private ring four
-//     steps deep, so that the one barrier per slice never waits on HBM latency.
+//     of a workgroup, go through double-buffered slices 128 (or, for the tall M-blocks, 64) columns deep (swizzled
+//     rows: conflict-free 16-byte reads); each hidden fragment read from LDS feeds NW MFMAs.  The weight fragments
+//     go through a wavefront-private ring four (two) steps deep, so that the one barrier per slice never waits on
+//     HBM latency.
+//   * The epilogue also reduces each row's logits over the workgroup's columns to softmax partials (maximum, its
+//     column, sum of exponentials at the row's temperature), so that no later pass has to read the logits for them.
 //   * All waits on the load counter are written by hand, by number (loads complete in issue order), and workgroup
 //     barriers carry no fence: with direct-to-LDS loads in flight every wait the compiler adds itself is a full
 //     drain of the counter, which would empty the weight pipeline at every slice.
