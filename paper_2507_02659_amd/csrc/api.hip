@@ -106,7 +106,7 @@ int ot_verify_init(const ot_verify_config* cfg, ot_ctx** out) {
 
   const size_t R = (size_t)c->max_rows, KQ = (size_t)c->max_K, Bm = (size_t)c->max_batch;
   bool ok = true;
-  if (c->dtype == OT_BF16) ok = ok && dev_alloc(c, &c->Wp, (size_t)c->Kp * c->Vp) && dev_alloc(c, &c->zeros, 32);
+  if (c->dtype == OT_BF16) ok = ok && dev_alloc(c, &c->Wp, (size_t)(c->Vp / 64) * (size_t)packed_tile_units(c->Kp / 32) * 8) && dev_alloc(c, &c->zeros, 32);
   else ok = ok && dev_alloc(c, &c->Wf, (size_t)c->d * c->V_t);
   ok = ok && dev_alloc(c, &c->dmap, (size_t)c->V_d) && dev_alloc(c, &c->tmap, (size_t)c->V_t);
   ok = ok && dev_alloc(c, &c->Z, R * (size_t)c->V_t);

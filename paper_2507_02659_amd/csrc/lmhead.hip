@@ -31,8 +31,9 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 
-// Packed layout (16-byte units): unit(((wt * nks + ks) * 4 + sub) * 64 + lane) holds
-//   W[ks*32 + 8*(lane/16) + e][wt*64 + sub*16 + lane%16], e = 0..7; zero outside [d, V_t].
+// Packed layout (16-byte units): unit(wt * packed_tile_units(nks) + (ks * 4 + sub) * 64 + lane) holds
+//   W[ks*32 + 8*(lane/16) + e][wt*64 + sub*16 + lane%16], e = 0..7; zero outside [d, V_t].  The gap between tiles is
+//   never read.
 __global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict__ W, int d, int V_t,
                                                      uint4* __restrict__ Wp, int nks, int64_t n_units) {
   const int64_t u = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -53,7 +54,7 @@ __global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict_
       w[e >> 1] |= x << (16 * (e & 1));
     }
   }
-  Wp[u] = make_uint4(w[0], w[1], w[2], w[3]);
+  Wp[(int64_t)wt * packed_tile_units(nks) + ((int64_t)ks * 4 + sub) * 64 + lane] = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -140,8 +141,8 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
   // the main loop then has no wavefront-dependent branch and every wavefront issues the same loads in the same order.
   const int t16 = active ? t16_own : n_wtiles * 4 - NW;
   const int row0 = m_block * (MT * 16);
-  // fragment (16-column tile t, step ks) sits at 16-byte unit (((t/4) * nks + ks) * 4 + t%4) * 64 + lane
-  const uint4* wp = Wp + ((int64_t)(t16 / 4) * nks * 4 + (t16 % 4)) * 64 + lane;
+  // fragment (16-column tile t, step ks) sits at 16-byte unit (t/4) * packed_tile_units(nks) + (ks * 4 + t%4) * 64 + lane
+  const uint4* wp = Wp + (int64_t)(t16 / 4) * packed_tile_units(nks) + (t16 % 4) * 64 + lane;
 
   f32x4 acc[MT][NW];
 #pragma unroll
@@ -383,7 +384,7 @@ __global__ __launch_bounds__(512) void lmhead_bf16_skinny_kernel(const uint16_t*
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wt = blockIdx.x;
   const int ks0 = (int)(((int64_t)nks * wave) / kWaves), ks1 = (int)(((int64_t)nks * (wave + 1)) / kWaves);
-  const uint4* wp = Wp + ((int64_t)wt * nks) * 256 + lane;
+  const uint4* wp = Wp + (int64_t)wt * packed_tile_units(nks) + lane;
   const int h_row = lane & 15, h_col = 8 * (lane >> 4);
   const bool h_ok = h_row < M;
   const uint16_t* hp = H + (int64_t)(h_ok ? h_row : 0) * d + h_col;
