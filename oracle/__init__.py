@@ -1,4 +1,5 @@
-"""CPU oracle for the verification step (NumPy float64 + integer Philox).
+"""CPU oracles (NumPy float64 + integer Philox): the verification step (verify, philox), the n-gram cache's life
+cycle (ngram_cache), the hybrid distillation loss (distill) and the adaptive-drafting rule (adaptive).
 
 TEST INFRASTRUCTURE ONLY.  Only tests/, __graft_entry__.smoke() and the
 cpu_baseline leg of bench.py may import this package.  It shares no code with
