@@ -113,8 +113,9 @@ int ot_verify_init(const ot_verify_config* cfg, ot_ctx** out) {
   ok = ok && dev_alloc(c, &c->tpart_max, R * c->ncht) && dev_alloc(c, &c->tpart_sum, R * c->ncht) && dev_alloc(c, &c->tpart_arg, R * c->ncht);
   if (c->dtype == OT_BF16) {
     const size_t nf = (size_t)(c->Vp / 256);
-    ok = ok && dev_alloc(c, &c->fpart_max, R * nf) && dev_alloc(c, &c->fpart_sum, R * nf) && dev_alloc(c, &c->fpart_arg, R * nf);
+    ok = ok && dev_alloc(c, &c->fpart, R * nf);
   }
+  ok = ok && dev_alloc(c, &c->proposal, R);
   ok = ok && dev_alloc(c, &c->dpart_max, KQ * c->nchd) && dev_alloc(c, &c->dpart_sum, KQ * c->nchd) && dev_alloc(c, &c->dpart_arg, KQ * c->nchd);
   ok = ok && dev_alloc(c, &c->row_max, R) && dev_alloc(c, &c->row_sum, R) && dev_alloc(c, &c->row_arg, R);
   ok = ok && dev_alloc(c, &c->drow_max, KQ) && dev_alloc(c, &c->drow_sum, KQ) && dev_alloc(c, &c->drow_arg, KQ);
@@ -191,6 +192,7 @@ static int step_impl(ot_ctx* ctx, ot_ngram_cache* cache, const ot_step_in* in, c
   a.row_max = ctx->row_max; a.row_sum = ctx->row_sum; a.row_arg = ctx->row_arg;
   a.drow_max = ctx->drow_max; a.drow_sum = ctx->drow_sum; a.drow_arg = ctx->drow_arg;
   a.fin = ctx->fin;
+  a.proposal = ctx->proposal;
   a.tile_r = ctx->tile_r; a.tile_p = ctx->tile_p;
   a.out = *o;
 
@@ -211,22 +213,23 @@ static int step_impl(ot_ctx* ctx, ot_ngram_cache* cache, const ot_step_in* in, c
   OT_MARK(0);
   if (e == hipSuccess && !from_logits) {
     if (ctx->dtype == OT_BF16) {
-      // the LM-head epilogue leaves per-tile softmax partials where its kernel supports it: the statistics kernel then
-      // merges those instead of reading the logits again
+      // Where its kernel supports it, the LM-head launch leaves per-tile softmax partials of the target rows (no second
+      // pass over the logits) and hosts the draft side of the step in extra workgroups: what follows it is then only
+      // the merge of those partials with the acceptance test, and the final draw.
       const int nfine = in->B <= kFusedMaxB ? lmhead_bf16_fused_partials(M, ctx->Vp) : 0;
       if (nfine > 0) {
         a.fused.row_off = in->row_off; a.fused.temperature = in->temperature; a.fused.B = in->B; a.fused.nfine = nfine;
-        a.fused.fmax = ctx->fpart_max; a.fused.fsum = ctx->fpart_sum; a.fused.farg = ctx->fpart_arg;
-        a.ncht = 1;
+        a.fused.part = ctx->fpart;
+        a.pre_translated = 1;
       }
       e = launch_lmhead_bf16(static_cast<const uint16_t*>(in->hidden), M, ctx->d, ctx->Wp, ctx->Kp, ctx->Vp, ctx->Z,
-                             ctx->V_t, a.ldz, ctx->zeros, &a.fused, st);
+                             ctx->V_t, a.ldz, ctx->zeros, &a.fused, a.pre_translated ? &a : nullptr, st);
     }
     else
       e = launch_lmhead_f32(static_cast<const float*>(in->hidden), M, ctx->d, ctx->Wf, ctx->Z, ctx->V_t, a.ldz, st);
   }
   OT_MARK(1);
-  if (e == hipSuccess) e = launch_softmax_stats(a, st);
+  if (e == hipSuccess && !a.pre_translated) e = launch_softmax_stats(a, st);
   OT_MARK(2);
   if (e == hipSuccess) e = launch_translate_accept(a, st);
   OT_MARK(3);

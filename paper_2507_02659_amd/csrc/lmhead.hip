@@ -22,7 +22,9 @@
 //     drain of the counter, which would empty the weight pipeline at every slice.
 // Operand roles: the weight fragment is MFMA operand A and the hidden fragment operand B, so a lane ends up with
 // four consecutive vocabulary columns of one row and stores them as one float4.
-#include "otv_internal.h"
+#include <algorithm>
+
+#include "translate.h"
 
 namespace otv {
 namespace {
@@ -98,7 +100,7 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
                                                                     int n_wtiles, float* __restrict__ Z, int V_t,
                                                                     int64_t ldz, int vec_store,
                                                                     const uint16_t* __restrict__ zeros, int m_blocks,
-                                                                    FusedStats fs) {
+                                                                    FusedStats fs, int n_role, StepArgs ds) {
   constexpr int kKSteps = KC / 32;                 // MFMA steps per slice
   constexpr int kCPR = KC / 8;                     // 16-byte chunks per slice row
   constexpr int kSliceChunks = MT * 16 * kCPR;
@@ -129,10 +131,19 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
   static_assert(WPG * 64 >= kFusedMaxB + 1, "one thread per sequence stages its row offset and temperature");
   static_assert((WPG & (WPG - 1)) == 0, "the mask below tells the compiler the range of the wavefront index");
   const int tid = threadIdx.x, wave = (tid >> 6) & (WPG - 1), lane = tid & 63;
+  // The first n_role workgroups of the launch do not multiply: they run the draft side of the step (softmax statistics
+  // of the draft rows, translation into the target vocabulary, parked proposals), which needs none of the logits, while
+  // the other workgroups stream the weights.  n_role is a multiple of 8, so the mapping below keeps its XCD.
+  if ((int)blockIdx.x < n_role) {
+    static_assert(sizeof(RoleLds) <= sizeof(sPatch) && WPG == kRoleWaves, "the draft side's scratch fits into the epilogue patch");
+    draft_side_workgroup<uint16_t>(ds, blockIdx.x, n_role, tid, reinterpret_cast<RoleLds*>(&sPatch[0][0]));
+    return;
+  }
+  const int wg = (int)blockIdx.x - n_role;
   // Workgroup id -> (column tile, M-block).  Consecutive ids go round-robin to the 8 XCDs, each with its own L2; the
   // M-blocks of one column tile get ids that land on the same XCD back to back, so that when M needs several
   // blocks their weight streams coincide in that XCD's L2 and HBM is still read once.
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int xcd = wg & 7, slot = wg >> 3;
   const int col_tile = (slot / m_blocks) * 8 + xcd, m_block = slot % m_blocks;
   if (col_tile * WPG * NW >= n_wtiles * 4) return;    // padding of the id space (whole workgroup)
   const int t16_own = (col_tile * WPG + wave) * NW;   // first 16-column tile of this wavefront
@@ -187,7 +198,7 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
   request(0, sA);
 #pragma unroll
   for (int s = 0; s < PF; ++s) fetch_w(min(s, nks - 1), s);
-  if (fs.fmax) {   // 4-byte direct loads: lane i of a wavefront fills entry 64*wave + i
+  if (fs.part) {   // 4-byte direct loads: lane i of a wavefront fills entry 64*wave + i
     if (wave * 64 <= fs.B) {
       __builtin_amdgcn_global_load_lds((glb_ptr_t)(fs.row_off + min(tid, fs.B)), (lds_ptr_t)(sRowOff + wave * 64), 4, 0,
                                        0);
@@ -254,7 +265,7 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
     }
     if (done) break;
   }
-  if (fs.fmax) {
+  if (fs.part) {
     // Row statistics of this workgroup's column tile, from the accumulators: per row the maximum, its lowest column
     // and sum exp((z - max)/T), first per wavefront (NW*16 columns), then merged over the wavefronts; one partial per
     // row and column tile goes to memory.  All LDS buffers of the main loop are free: every wavefront has passed the
@@ -330,8 +341,9 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
           for (int g = 0; g < 4; ++g)
             if (m4[g] != -INFINITY) sum += s4[g] * __builtin_amdgcn_exp2f((m4[g] - best) * sc);
         }
-        const int64_t o = (int64_t)(row0 + h * 16 + tid) * fs.nfine + col_tile;
-        fs.fmax[o] = best; fs.fsum[o] = sum; fs.farg[o] = barg;
+        Partial out;
+        out.mx = best; out.arg = barg; out.sum = (double)sum;
+        fs.part[(int64_t)(row0 + h * 16 + tid) * fs.nfine + col_tile] = out;
       }
       if (h + kStatMT < MT) lds_barrier();         // the next group overwrites the scratch
     }
@@ -456,15 +468,37 @@ __global__ __launch_bounds__(256) void lmhead_f32_kernel(const float* __restrict
   Z[(int64_t)m * ldz + n] = acc;
 }
 
+// Workgroups of the launch that run the draft side: as many as the draft logits need to be read well inside the
+// weight stream's time (one workgroup reads on the order of 8 MB in the time an M-block streams the weights), at
+// most one per sequence, and where possible no more than the compute units the last round of multiplying workgroups
+// leaves idle (one workgroup per compute unit), so that they add no round.  A multiple of 8: the XCD mapping holds.
+int draft_side_workgroups(int n_gemm_wgs, const StepArgs& ds) {
+  const int64_t bytes = (int64_t)ds.K * ds.V_d * (ds.dtype == OT_BF16 ? 2 : 4);
+  int want = 8 * (int)std::max<int64_t>(1, (bytes + (8 << 20) - 1) / (8 << 20));
+  const int idle = (256 - n_gemm_wgs % 256) % 256;
+  want = std::min(want, std::max(8, idle / 8 * 8));
+  want = std::min(want, (ds.B + 7) / 8 * 8);
+  return std::min(want, 64);
+}
+
 template <int MT, int PF, int WPG, int KC, int NW>
 hipError_t launch_wide(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
-                       int64_t ldz, const uint16_t* zeros, const FusedStats& fs, hipStream_t stream) {
+                       int64_t ldz, const uint16_t* zeros, const FusedStats& fs, const StepArgs* draft_side,
+                       hipStream_t stream) {
   const int nks = Kp / 32, n_wtiles = Vp / kGemmColsPerWave;
   const int m_blocks = ceil_div(M, MT * 16);
-  dim3 grid(ceil_div(ceil_div(n_wtiles * 4, WPG * NW), 8) * 8 * m_blocks), block(WPG * 64);
+  const int col_tiles = ceil_div(n_wtiles * 4, WPG * NW);
+  StepArgs ds{};
+  int n_role = 0;
+  if (draft_side && fs.part) {
+    ds = *draft_side;
+    n_role = draft_side_workgroups(col_tiles * m_blocks, ds);
+  }
+  dim3 grid(n_role + ceil_div(col_tiles, 8) * 8 * m_blocks), block(WPG * 64);
   const int vec_store = (ldz % 4 == 0) && (reinterpret_cast<uintptr_t>(Z) % 16 == 0);
   hipLaunchKernelGGL((lmhead_bf16_wide_kernel<MT, PF, WPG, KC, NW>), grid, block, 0, stream, H, M, d,
-                     reinterpret_cast<const uint4*>(Wp), nks, n_wtiles, Z, V_t, ldz, vec_store, zeros, m_blocks, fs);
+                     reinterpret_cast<const uint4*>(Wp), nks, n_wtiles, Z, V_t, ldz, vec_store, zeros, m_blocks, fs, n_role,
+                     ds);
   return hipGetLastError();
 }
 
@@ -483,11 +517,12 @@ int lmhead_bf16_fused_partials(int M, int Vp) {
 }
 
 hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
-                              int64_t ldz, const uint16_t* zeros, const FusedStats* fused, hipStream_t stream) {
+                              int64_t ldz, const uint16_t* zeros, const FusedStats* fused, const StepArgs* draft_side,
+                              hipStream_t stream) {
   if (M == 0) return hipSuccess;
   const int tiles = ceil_div(M, 16);
   FusedStats fs{};
-  if (fused && fused->fmax) {
+  if (fused && fused->part) {
     if (fused->nfine != lmhead_bf16_fused_partials(M, Vp) || fused->nfine == 0 || fused->B < 1 || fused->B > kFusedMaxB)
       return hipErrorInvalidValue;
     fs = *fused;
@@ -498,10 +533,10 @@ hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* W
                        reinterpret_cast<const uint4*>(Wp), nks, Z, V_t, ldz);
     return hipGetLastError();
   }
-  if (tiles <= 2) return launch_wide<2, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
-  if (tiles <= 4) return launch_wide<4, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
-  if (tiles <= 6) return launch_wide<6, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
-  if (tiles <= 9) return launch_wide<9, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
+  if (tiles <= 2) return launch_wide<2, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
+  if (tiles <= 4) return launch_wide<4, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
+  if (tiles <= 6) return launch_wide<6, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
+  if (tiles <= 9) return launch_wide<9, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
   // More than 144 rows run as several M-blocks per column tile; their weight streams meet in one L2.  This regime is
   // bound by the L2 -> LDS traffic and by LDS reads, and the time of an M-block was measured to grow almost in
   // proportion to its height (about 1.3 row tiles of fixed cost per block: 144, 256, 288 rows take 150, 251, 284 us at
@@ -514,12 +549,12 @@ hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* W
     if (cost <= best_cost) { best_cost = cost; best_mt = mt; }
   }
   switch (best_mt) {
-    case 10: return launch_wide<10, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
-    case 12: return launch_wide<12, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
-    case 14: return launch_wide<14, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
-    case 16: return launch_wide<16, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
-    case 18: return launch_wide<18, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
-    default: return launch_wide<9, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, stream);
+    case 10: return launch_wide<10, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
+    case 12: return launch_wide<12, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
+    case 14: return launch_wide<14, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
+    case 16: return launch_wide<16, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
+    case 18: return launch_wide<18, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
+    default: return launch_wide<9, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
   }
 }
 

@@ -23,8 +23,8 @@ struct ot_ctx {
   float *tpart_max = nullptr, *dpart_max = nullptr, *row_max = nullptr, *drow_max = nullptr;
   double *tpart_sum = nullptr, *dpart_sum = nullptr, *row_sum = nullptr, *drow_sum = nullptr;
   int32_t *tpart_arg = nullptr, *dpart_arg = nullptr, *row_arg = nullptr, *drow_arg = nullptr;
-  float *fpart_max = nullptr, *fpart_sum = nullptr;   // [max_rows, Vp/256] partials from the LM-head epilogue (bf16)
-  int32_t* fpart_arg = nullptr;
+  otv::Partial* fpart = nullptr;      // [max_rows, Vp/256] softmax partials from the LM-head epilogue (bf16)
+  otv::RowProposal* proposal = nullptr;   // [max_rows] translated proposals parked between two kernels
   double *tile_r = nullptr, *tile_p = nullptr;
   otv::FinalInfo* fin = nullptr;
   void* loss_rows = nullptr;          // [max_rows] records of kLossRowBytes: per-token constants of the loss kernels

@@ -67,17 +67,40 @@ struct FinalInfo {
   double mx, invT, invS, mxq, invTd, invSq;
 };
 
+// One mapped position of a translated proposal, parked in memory between the kernel that translates (it needs only the
+// drafter's side of the step) and the kernel that tests acceptance (it needs the target's logits).  Entry
+// row_off[b] + j belongs to mapped position j of sequence b; j == n_mapped is filled when the proposal was cut by an
+// untranslatable id (its `start` is that id's draft position).
+struct RowProposal {
+  int32_t t;             // target id t_j, or -1 beyond the proposal
+  int32_t start, len;    // draft positions covered
+  int32_t t_pre;         // direct image of the draft id at `start` (Eq. 2, prefix case), or -1
+  int32_t argq;          // argmax of the draft row at `start`
+  float mxq;             // maximum of that row
+  double lq;             // log q'(t_j): sum of the sub-tokens' log-probabilities (Eq. 1)
+  double lq_first;       // log q(d) of the draft id at `start`
+  double Sq;             // sum of exponentials of that row
+  int32_t pad[4];
+};
+static_assert(sizeof(RowProposal) == 64, "one record per 64 bytes");
+
+// Softmax partial of one row over one column tile: maximum, its lowest column, sum of exp((z - mx) / T).
+struct alignas(16) Partial {
+  float mx;
+  int32_t arg;
+  double sum;
+};
+static_assert(sizeof(Partial) == 16, "stored and loaded as one 16-byte vector");
+
 // Softmax partials emitted by the LM-head epilogue (one per row and column tile of the kernel), so that the logits
-// need not be read again for their row statistics.  fmax == nullptr: not wanted.
+// need not be read again for their row statistics.  part == nullptr: not wanted.
 constexpr int kFusedMaxB = 255;      // sequences whose row offsets and temperatures the LM-head kernel stages in LDS
 struct FusedStats {
   const int32_t* row_off;            // [B + 1]
   const float* temperature;          // [B]
   int32_t B;
-  int32_t nfine;                     // partials per row (row stride of the arrays below)
-  float* fmax;                       // [M, nfine] maximum of the tile's logits of the row
-  float* fsum;                       // [M, nfine] sum of exp((z - fmax) / T_b) over the tile
-  int32_t* farg;                     // [M, nfine] lowest column holding fmax
+  int32_t nfine;                     // partials per row (row stride of `part`)
+  Partial* part;                     // [M, nfine]
 };
 
 struct StepArgs {
@@ -105,6 +128,9 @@ struct StepArgs {
   float* dpart_max; double* dpart_sum; int32_t* dpart_arg;   // [K, nchd]
   float* row_max; double* row_sum; int32_t* row_arg;         // [M]
   float* drow_max; double* drow_sum; int32_t* drow_arg;      // [K]
+  RowProposal* proposal; // [M] written by the draft side when it runs apart from the acceptance test
+  int32_t pre_translated; // the draft side has already run (inside the LM-head launch): `proposal`, drow_* and the
+                         // translation outputs are final; the acceptance kernel only merges the LM head's partials
   FinalInfo* fin;        // [B]
   int32_t ntiles;        // residual tiles per row
   double* tile_r; double* tile_p;                            // [B, ntiles]
@@ -118,10 +144,13 @@ hipError_t launch_pack_w_bf16(const uint16_t* W, int d, int V_t, uint16_t* Wp, i
 // Partials per row that launch_lmhead_bf16 emits for M rows of a Vp-column (padded) head; 0: that shape runs a
 // kernel without the fused statistics.
 int lmhead_bf16_fused_partials(int M, int Vp);
-// `fused` may be nullptr or have fmax == nullptr (no statistics); otherwise fused->nfine must be
-// lmhead_bf16_fused_partials(M, Vp) > 0 and fused->B <= kFusedMaxB.
+// `fused` may be nullptr or have part == nullptr (no statistics); otherwise fused->nfine must be
+// lmhead_bf16_fused_partials(M, Vp) > 0 and fused->B <= kFusedMaxB.  With fused statistics and `draft_side` not
+// nullptr, extra workgroups of the same launch run the draft side of the step (draft row statistics, translation,
+// parked proposals: everything of *draft_side that does not need the logits), hidden behind the weight stream.
 hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
-                              int64_t ldz, const uint16_t* zeros, const FusedStats* fused, hipStream_t stream);
+                              int64_t ldz, const uint16_t* zeros, const FusedStats* fused, const StepArgs* draft_side,
+                              hipStream_t stream);
 hipError_t launch_lmhead_f32(const float* H, int M, int d, const float* W, float* Z, int V_t, int64_t ldz,
                              hipStream_t stream);
 hipError_t launch_softmax_stats(const StepArgs& a, hipStream_t stream);

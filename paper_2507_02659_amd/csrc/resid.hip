@@ -25,10 +25,12 @@ static_assert(kPer == 4, "the fixed summation trees below are written for 4 ids 
 // p(v) and q'(v) of Eq. 2 at the final row of one sequence.
 struct FinalRow {
   const float* z;
-  double mx, invT, invS;
+  float mx, sc_hi, sc_lo;        // row maximum; log2(e) / T split into two floats
+  double invS;
   const void* zq;
   int dtype;
-  double mxq, invTd, invSq;
+  float mxq, scq_hi, scq_lo;     // the same for the draft row
+  double invSq;
   int argq;
   bool greedy_draft;
   bool residual;
@@ -36,14 +38,22 @@ struct FinalRow {
   int t_ng, t_pre;
   double pi, q_pre;
 
-  __device__ inline double p_of(float zv) const { return exp_neg_fast(((double)zv - mx) * invT) * invS; }
+  // exp((x - max) / T) / S for x <= max.  The exponent goes through the hardware 2^x in binary32: the difference to the
+  // row maximum is formed in binary32 (its rounding is random, not a bias), the scale is applied as a two-float
+  // product so that its own rounding does not tilt the whole row, and the normaliser is applied in binary64.  Relative
+  // error about 2e-7 per value, unbiased; the running sums over the vocabulary are binary64.
+  __device__ static inline double softmax_term(float x, float mx, float sc_hi, float sc_lo, double invS) {
+    const float d = x - mx;
+    return (double)__builtin_amdgcn_exp2f(fmaf(d, sc_hi, d * sc_lo)) * invS;
+  }
+  __device__ inline double p_of(float zv) const { return softmax_term(zv, mx, sc_hi, sc_lo, invS); }
   __device__ inline float draft_logit(int dv) const {
     return dtype == OT_BF16 ? bf16_to_f32(static_cast<const uint16_t*>(zq)[dv]) : static_cast<const float*>(zq)[dv];
   }
   // q'(v) given the draft id dv = tmap[v] (or -1) and, when dv >= 0 and the draft is not greedy, its logit
   __device__ inline double qprime(int v, int dv, float xq) const {
     double q = 0.0;
-    if (dv >= 0) q = greedy_draft ? ((dv == argq) ? 1.0 : 0.0) : exp_neg_fast(((double)xq - mxq) * invTd) * invSq;
+    if (dv >= 0) q = greedy_draft ? ((dv == argq) ? 1.0 : 0.0) : softmax_term(xq, mxq, scq_hi, scq_lo, invSq);
     if (v == t_pre) q = q_pre;
     if (v == t_ng) q = pi;       // the n-gram case of Eq. 2 wins when both name the same id
     return q;
@@ -53,13 +63,14 @@ struct FinalRow {
 __device__ inline FinalRow make_final_row(const StepArgs& a, const FinalInfo& f) {
   FinalRow R;
   R.z = a.Z + (int64_t)f.row * a.ldz;
-  R.mx = f.mx; R.invT = f.invT; R.invS = f.invS;
+  const double sc = f.invT * 1.4426950408889634, scq = f.invTd * 1.4426950408889634;
+  R.mx = (float)f.mx; R.sc_hi = (float)sc; R.sc_lo = (float)(sc - (double)R.sc_hi); R.invS = f.invS;
   R.residual = f.mode == 3;
   R.dtype = a.dtype;
   R.tmap = a.tmap;
   R.t_ng = f.t_ng; R.t_pre = f.t_pre; R.pi = f.pi; R.q_pre = f.q_pre;
   R.zq = static_cast<const char*>(a.draft_logits) + (size_t)f.drow * a.V_d * (a.dtype == OT_BF16 ? 2 : 4);
-  R.mxq = f.mxq; R.invTd = f.invTd; R.invSq = f.invSq; R.argq = f.argq; R.greedy_draft = f.greedy_draft != 0;
+  R.mxq = (float)f.mxq; R.scq_hi = (float)scq; R.scq_lo = (float)(scq - (double)R.scq_hi); R.invSq = f.invSq; R.argq = f.argq; R.greedy_draft = f.greedy_draft != 0;
   return R;
 }
 
@@ -121,17 +132,18 @@ __global__ __launch_bounds__(kThreads) void resid_sums_kernel(StepArgs a) {
 __global__ __launch_bounds__(kThreads) void resid_pick_kernel(StepArgs a) {
   const int b = blockIdx.x, tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
-  const FinalInfo f = a.fin[b];
-  if (f.mode == 0) return;
-  FinalRow R = make_final_row(a, f);
   __shared__ double s_w[2][kThreads / 64];
   extern __shared__ double s_tiles[];       // [2][ntiles]: residual masses, then p masses
   __shared__ int s_pick, s_fallback, s_first, s_lastnz;
   __shared__ double s_base, s_target;
+  // the tile masses do not depend on the outcome record: both loads are in flight together
   for (int t = tid; t < a.ntiles; t += kThreads) {
     s_tiles[t] = a.tile_r[(int64_t)b * a.ntiles + t];
     s_tiles[a.ntiles + t] = a.tile_p[(int64_t)b * a.ntiles + t];
   }
+  const FinalInfo f = a.fin[b];
+  if (f.mode == 0) return;
+  FinalRow R = make_final_row(a, f);
   __syncthreads();
   if (wave == 0) {
     // Running mass over the tiles in ascending order, in place: wavefront scan of 64 tiles at a time plus a carry.

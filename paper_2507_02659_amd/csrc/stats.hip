@@ -117,57 +117,7 @@ __device__ inline void chunk_stats(const T* __restrict__ x_row, int V, int c, fl
   }
 }
 
-// Merges the fine partials that the LM-head epilogue left for one row (one per 256-column tile) into the row's
-// single partial: maximum, lowest column of the maximum, sum of exp((z - max)/T).  One workgroup per row; the
-// partial sums are rescaled and added in double, in a fixed order.
-__device__ inline void merge_fused_row(const FusedStats& f, int row, float scale, float* __restrict__ pmax,
-                                       double* __restrict__ psum, int32_t* __restrict__ parg) {
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int64_t o = (int64_t)row * f.nfine;
-  float best = -INFINITY;
-  int best_i = 0x7FFFFFFF;
-  for (int c = tid; c < f.nfine; c += kStatThreads) {
-    const float m = f.fmax[o + c];
-    const int ai = f.farg[o + c];
-    if (m > best || (m == best && ai < best_i)) { best = m; best_i = ai; }
-  }
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) {
-    const float ob = __shfl_xor(best, off);
-    const int oi = __shfl_xor(best_i, off);
-    if (ob > best || (ob == best && oi < best_i)) { best = ob; best_i = oi; }
-  }
-  __shared__ float s_max[kStatThreads / 64];
-  __shared__ int s_idx[kStatThreads / 64];
-  __shared__ double s_sum[kStatThreads / 64];
-  if (lane == 0) { s_max[wave] = best; s_idx[wave] = best_i; }
-  __syncthreads();
-  best = s_max[0]; best_i = s_idx[0];
-#pragma unroll
-  for (int w = 1; w < kStatThreads / 64; ++w) {
-    if (s_max[w] > best || (s_max[w] == best && s_idx[w] < best_i)) { best = s_max[w]; best_i = s_idx[w]; }
-  }
-  double sum = 0.0;
-  for (int c = tid; c < f.nfine; c += kStatThreads) {
-    const float m = f.fmax[o + c];
-    if (m != -INFINITY) sum += (double)f.fsum[o + c] * (double)__builtin_amdgcn_exp2f((m - best) * scale);
-  }
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
-  if (lane == 0) s_sum[wave] = sum;
-  __syncthreads();
-  if (tid == 0) {
-    double total = s_sum[0];
-#pragma unroll
-    for (int w = 1; w < kStatThreads / 64; ++w) total += s_sum[w];
-    pmax[row] = best;
-    psum[row] = total;
-    parg[row] = best_i;
-  }
-}
-
-// Rows 0..M-1 are target rows, rows M..M+K-1 draft rows.  TD is the draft logits' storage type.  With fused
-// statistics (a.fused.nfine > 0, a.ncht == 1) a target row takes one workgroup that merges the LM head's partials.
+// Rows 0..M-1 are target rows, rows M..M+K-1 draft rows.  TD is the draft logits' storage type.
 template <typename TD, bool kAlignedT, bool kAlignedD>
 __global__ __launch_bounds__(kStatThreads) void softmax_stats_kernel(StepArgs a) {
   const int n_target = a.M * a.ncht;                 // workgroups 0 .. n_target-1 take target chunks, the rest draft chunks
@@ -176,10 +126,6 @@ __global__ __launch_bounds__(kStatThreads) void softmax_stats_kernel(StepArgs a)
     const int b = find_sequence(a.row_off, a.B, row, 0);
     const float T_b = a.temperature[b];
     const float scale = T_b > 0.f ? kLog2e / T_b : kLog2e;
-    if (a.fused.nfine > 0) {
-      merge_fused_row(a.fused, row, scale, a.tpart_max, a.tpart_sum, a.tpart_arg);
-      return;
-    }
     chunk_stats<float, kAlignedT>(a.Z + (int64_t)row * a.ldz, a.V_t, c, scale, a.tpart_max, a.tpart_sum, a.tpart_arg,
                                   (int64_t)row * a.ncht + c);
   } else {
