@@ -260,11 +260,11 @@ int ot_verify_workspace(ot_ctx* ctx, ot_workspace_view* view);
  * ot_verify_profile_read synchronises the stream, adds the elapsed milliseconds of the steps run since the
  * last read into ms[0 .. OT_N_STAGES) (overwriting it), stores the number of steps in *n_steps and resets.    */
 #define OT_STAGE_LM_HEAD          0   /* z = h . W                                                            */
-#define OT_STAGE_SOFTMAX_STATS    1   /* softmax statistics of the target rows and of the draft rows          */
+#define OT_STAGE_SOFTMAX_STATS    1   /* softmax statistics of the target and draft rows; 0 when the LM-head
+                                         launch computes them itself                                          */
 #define OT_STAGE_TRANSLATE_ACCEPT 2   /* translation scan + n-gram probes (Eq. 1), acceptance ratios, Philox  */
-#define OT_STAGE_RESID_SUMS       3   /* partial masses of max(0, p - q') (Eq. 2) at the final row            */
-#define OT_STAGE_RESID_PICK       4   /* inverse-CDF pick of the final token                                  */
-#define OT_N_STAGES               5
+#define OT_STAGE_RESIDUAL_DRAW    3   /* masses of max(0, p - q') (Eq. 2) at the final row, inverse-CDF draw  */
+#define OT_N_STAGES               4
 int ot_verify_profile(ot_ctx* ctx, int32_t enable);
 int ot_verify_profile_read(ot_ctx* ctx, float* ms, int32_t* n_steps);
 

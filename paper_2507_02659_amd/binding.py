@@ -20,8 +20,8 @@ OT_ERR_NGRAM, OT_ERR_CTX_MISMATCH, OT_ERR_HIP, OT_ERR_NOMEM = -5, -6, -7, -8
 OT_BF16, OT_F32 = 0, 1
 OT_FLAG_UNMAPPABLE, OT_FLAG_RESID_ZERO, OT_FLAG_BAD_ID = 1, 2, 4
 OT_MAX_NGRAM_LEN, OT_MAX_K = 8, 63
-OT_N_STAGES = 5
-STAGE_NAMES = ("lm_head", "softmax_stats", "translate_accept", "resid_sums", "resid_pick")
+OT_N_STAGES = 4
+STAGE_NAMES = ("lm_head", "softmax_stats", "translate_accept", "residual_draw")
 
 OT_EVICT_NONE, OT_EVICT_LRU, OT_EVICT_LFU = 0, 1, 2
 OT_LAMBDA_FIXED, OT_LAMBDA_TARGET_PROB = 0, 1

@@ -1,115 +1,14 @@
-// Acceptance test of a translated proposal (Algorithm 1, rejection-sampling step), one workgroup of 768 threads per
-// sequence, preceded in the same kernel by whatever of the step has not run yet.
-//
-// Two callers.  After an LM-head launch that hosted the draft side and left per-tile softmax partials, the kernel only
-// merges those partials (one wavefront per target row) and fetches the parked proposal.  Otherwise the three jobs that
-// do not depend on each other run in different wavefronts of the workgroup at the same time: threads 0-255 merge the
-// target rows' chunk partials, threads 256-511 the draft rows' partials, threads 512-767 fetch the drafted ids, their
-// logits and direct images and probe the n-gram table (Section "Cross-vocabulary N-gram Cache", Eq. 1); one barrier
-// later the walk and the acceptance test need only LDS and one gather of z[t_j].
-//
-// Acceptance.  Lane j of the first wavefront owns mapped position j: it forms p_j(t_j), the ratio min(1, p/q') and its
-// Philox uniform; acceptance tests at different positions are independent given (u_j, p_j(t_j), q'_j), so "stop at the
-// first rejection" is a ballot and a find-first-set, not a loop.  It also writes what the final-token kernels need
-// (FinalInfo).
-#include "translate.h"
+// Translation and acceptance test in one launch, for steps whose draft side has not run inside the LM-head launch:
+// one workgroup of 768 threads per sequence.  The three jobs that do not depend on each other run in different
+// wavefronts of the workgroup at the same time: threads 0-255 merge the target rows' chunk partials, threads 256-511
+// the draft rows' partials, threads 512-767 fetch the drafted ids, their logits and direct images and probe the n-gram
+// table (Section "Cross-vocabulary N-gram Cache", Eq. 1); one barrier later the walk and the acceptance test
+// (Algorithm 1, rejection-sampling step) need only LDS and one gather of z[t_j].  The outcome record of every sequence
+// goes to memory for the launch that draws the final token.
+#include "accept.h"
 
 namespace otv {
 namespace {
-
-// Merges the chunk partials of up to 64 rows starting at row `first`: 4 threads per row, every 4th chunk each,
-// combined in a fixed order.  Thread 4*r publishes row r's (max, sum, argmax) to LDS and to the workspace.
-__device__ inline void merge_partials(const float* __restrict__ pmax, const double* __restrict__ psum,
-                                      const int32_t* __restrict__ parg, int nch, int first, int n_rows, double invT,
-                                      float* s_mx, double* s_S, int* s_arg, float* g_mx, double* g_S, int32_t* g_arg,
-                                      int local_tid) {
-  const int row = local_tid >> 2, part = local_tid & 3;
-  const bool live = row < n_rows;
-  const int64_t o = (int64_t)(first + (live ? row : 0)) * nch;
-  float mx = -INFINITY;
-  int arg = 0x7FFFFFFF;
-  if (live) {
-    for (int c = part; c < nch; c += 4) {
-      const float m = pmax[o + c];
-      const int ai = parg[o + c];
-      if (m > mx || (m == mx && ai < arg)) { mx = m; arg = ai; }
-    }
-  }
-#pragma unroll
-  for (int off = 1; off <= 2; off <<= 1) {
-    const float om = __shfl_xor(mx, off);
-    const int oa = __shfl_xor(arg, off);
-    if (om > mx || (om == mx && oa < arg)) { mx = om; arg = oa; }
-  }
-  double S = 0.0;
-  if (live) {
-    for (int c = part; c < nch; c += 4) S += psum[o + c] * exp(((double)pmax[o + c] - (double)mx) * invT);
-  }
-  const double s1 = __shfl_xor(S, 1);
-  const double lo = (part & 1) ? s1 + S : S + s1;          // (part0 + part1) or (part2 + part3), same order in both lanes
-  const double s2 = __shfl_xor(lo, 2);
-  const double total = (part & 2) ? s2 + lo : lo + s2;     // (p0 + p1) + (p2 + p3)
-  if (live && part == 0) {
-    s_mx[row] = mx; s_S[row] = total; s_arg[row] = arg;
-    g_mx[first + row] = mx; g_S[first + row] = total; g_arg[first + row] = arg;
-  }
-}
-
-// Merges the LM head's partials of one target row (nfine of them, one per column tile): called by a whole wavefront.
-// A lane requests eight 16-byte partials at a time before it looks at any of them (one round trip to memory for up
-// to 512 tiles) and keeps a running maximum with the sum rescaled to it; the lanes are then merged by shuffles.  Sums
-// are rescaled and added in binary64, in a fixed order.  Lane 0 publishes the row's (max, sum, argmax) to LDS and to
-// the workspace.
-__device__ inline void merge_fused_row(const Partial* __restrict__ part, int nfine, int row, double invT, int lane,
-                                       float* s_mx, double* s_S, int* s_arg, int at, float* g_mx, double* g_S,
-                                       int32_t* g_arg) {
-  const uint4* p = reinterpret_cast<const uint4*>(part + (int64_t)row * nfine);
-  const float sc = (float)invT * kLog2eF;
-  RunStat r;
-  for (int c0 = 0; c0 < nfine; c0 += 512) {
-    uint4 raw[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int c = c0 + j * 64 + lane;
-      raw[j] = c < nfine ? p[c] : make_uint4(0xFF800000u, 0x7FFFFFFFu, 0u, 0u);     // (-inf, no column, 0.0)
-    }
-    float bm = -INFINITY;
-    int bi = 0x7FFFFFFF;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const float m = __uint_as_float(raw[j].x);
-      const int ai = (int)raw[j].y;
-      if (m > bm || (m == bm && ai < bi)) { bm = m; bi = ai; }
-    }
-    if (bm > r.mx || (bm == r.mx && bi < r.arg)) {
-      r.sum *= (double)__builtin_amdgcn_exp2f((r.mx - bm) * sc);
-      r.mx = bm; r.arg = bi;
-    }
-    if (r.mx != -INFINITY) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const float m = __uint_as_float(raw[j].x);
-        const double sum = __hiloint2double((int)raw[j].w, (int)raw[j].z);
-        r.sum += sum * (double)__builtin_amdgcn_exp2f((m - r.mx) * sc);              // empty: 0 * exp2(-inf) = 0
-      }
-    }
-  }
-  float mx = r.mx;
-  int arg = r.arg;
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) {
-    const float om = __shfl_xor(mx, off);
-    const int oa = __shfl_xor(arg, off);
-    if (om > mx || (om == mx && oa < arg)) { mx = om; arg = oa; }
-  }
-  double S = r.mx == -INFINITY ? 0.0 : r.sum * (double)__builtin_amdgcn_exp2f((r.mx - mx) * sc);
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) S += __shfl_xor(S, off);
-  if (lane == 0) {
-    s_mx[at] = mx; s_S[at] = S; s_arg[at] = arg;
-    g_mx[row] = mx; g_S[row] = S; g_arg[row] = arg;
-  }
-}
 
 __global__ __launch_bounds__(768) void translate_accept_kernel(StepArgs a) {
   const int b = blockIdx.x, tid = threadIdx.x;
@@ -123,149 +22,36 @@ __global__ __launch_bounds__(768) void translate_accept_kernel(StepArgs a) {
   __shared__ double s_pS[64];
   __shared__ int s_parg[64];
 
-  // ---- loads that depend on nothing but b
   const float T = a.temperature[b];
   const float Td = a.draft_temperature ? a.draft_temperature[b] : T;
   const uint64_t sid = a.seq_id[b];
   const double invT = T > 0.f ? 1.0 / (double)T : 1.0;
   const double invTd = Td > 0.f ? 1.0 / (double)Td : 1.0;
 
+  draft_lds_reset(&s_d, tid);
+  __syncthreads();
+  if (role == 0) {
+    merge_partials(a.tpart_max, a.tpart_sum, a.tpart_arg, a.ncht, r0, k + 1, invT, s_pmx, s_pS, s_parg, a.row_max,
+                   a.row_sum, a.row_arg, g);
+  } else if (role == 1) {
+    merge_partials(a.dpart_max, a.dpart_sum, a.dpart_arg, a.nchd, q0, k, invTd, s_d.qmx, s_d.qS, s_d.qarg, a.drow_max,
+                   a.drow_sum, a.drow_arg, g);
+  } else {
+    fetch_ids_and_probe(a, q0, k, g, 256, &s_d);
+  }
+  __syncthreads();
+  if (tid >= 64) return;          // the rest is one wavefront's work
   LaneProposal P;
   P.t = -1; P.start = -1; P.L = 0; P.lq = 0.0; P.t_pre = -1; P.argq = -1; P.mxq = 0.f; P.Sq = 1.0; P.lq_first = 0.0;
   P.m = 0; P.flags = 0;
-  bool bad = false;
-  float z_tok = 0.f;              // z[row j, t_j]
-  if (a.pre_translated) {
-    // the proposal is parked in memory; its loads go out first so that the gather of z[t_j] follows them early and is
-    // under way while the partials are merged
-    if (tid < 64) {
-      if (lane <= k) fetch_proposal(a.proposal + r0 + lane, &P);
-      P.m = a.out.n_mapped[b];
-      P.flags = a.out.flags[b];
-      if (!(P.flags & OT_FLAG_BAD_ID) && lane < P.m && T > 0.f) z_tok = a.Z[(int64_t)(r0 + lane) * a.ldz + P.t];
-    }
-    for (int row = tid >> 6; row <= k; row += 12)
-      merge_fused_row(a.fused.part, a.fused.nfine, r0 + row, invT, lane, s_pmx, s_pS, s_parg, row, a.row_max, a.row_sum,
-                      a.row_arg);
-    __syncthreads();
-    bad = (P.flags & OT_FLAG_BAD_ID) != 0;
+  if (s_d.bad) {
+    translate_bad_sequence(a, b, r0, k, lane);
+    P.flags = OT_FLAG_BAD_ID;
   } else {
-    draft_lds_reset(&s_d, tid);
-    __syncthreads();
-    if (role == 0) {
-      merge_partials(a.tpart_max, a.tpart_sum, a.tpart_arg, a.ncht, r0, k + 1, invT, s_pmx, s_pS, s_parg, a.row_max,
-                     a.row_sum, a.row_arg, g);
-    } else if (role == 1) {
-      merge_partials(a.dpart_max, a.dpart_sum, a.dpart_arg, a.nchd, q0, k, invTd, s_d.qmx, s_d.qS, s_d.qarg, a.drow_max,
-                     a.drow_sum, a.drow_arg, g);
-    } else {
-      fetch_ids_and_probe(a, q0, k, g, 256, &s_d);
-    }
-    __syncthreads();
-    bad = s_d.bad != 0;
-    if (bad && tid < 64) translate_bad_sequence(a, b, r0, k, lane);
+    translate_walk(a, b, r0, k, q0, Td, invTd, lane, &s_d, &P);
   }
-
-  FinalInfo fin;
-  fin.mode = 0; fin.row = r0; fin.drow = 0; fin.t_ng = -1; fin.t_pre = -1; fin.argq = -1; fin.greedy_draft = 0;
-  fin.pad = 0; fin.pi = 0.0; fin.q_pre = 0.0; fin.u2 = 0.0;
-  fin.mx = 0.0; fin.invT = 1.0; fin.invS = 1.0; fin.mxq = 0.0; fin.invTd = 1.0; fin.invSq = 1.0;
-
-  if (tid >= 64) return;          // the rest is one wavefront's work
-  if (bad) {                      // a drafted id outside [0, V_d): the sequence emits nothing
-    if (lane <= k) {
-      a.out.out_tokens[r0 + lane] = -1;
-      a.out.p_tok[r0 + lane] = 0.f; a.out.ratio[r0 + lane] = 0.f;
-    }
-    if (lane == 0) {
-      a.out.n_accept[b] = 0; a.out.n_accept_draft[b] = 0; a.out.n_emit[b] = 0; a.out.hits_accepted[b] = 0;
-      a.fin[b] = fin;
-    }
-    return;
-  }
-  if (!a.pre_translated) translate_walk(a, b, r0, k, q0, Td, invTd, lane, &s_d, &P);
-  const int m = P.m, flags = P.flags;
-  const int t_j = P.t, L_j = P.L;
-
-  // ---- acceptance test of mapped position `lane`
-  const uint32_t k0 = (uint32_t)a.seed, k1 = (uint32_t)(a.seed >> 32);
-  const float mx = lane <= k ? s_pmx[lane] : 0.f;
-  const double S = lane <= k ? s_pS[lane] : 1.0;
-  const int arg = lane <= k ? s_parg[lane] : 0;
-  bool ok = true;               // lanes >= m do not veto
-  double pt = 0.0, qp = 0.0, ratio = 0.0;
-  uint32_t w[4] = {0, 0, 0, 0};  // the uniforms of row `lane`: word 0 tests mapped position `lane`, word 1 draws its final token
-  if (T > 0.f && lane <= k) philox4x32_10((uint32_t)lane, a.step, (uint32_t)sid, (uint32_t)(sid >> 32), k0, k1, w);
-  if (lane < m) {
-    qp = exp(P.lq);
-    if (T > 0.f) {
-      const double z = (double)(a.pre_translated ? z_tok : a.Z[(int64_t)(r0 + lane) * a.ldz + t_j]);
-      pt = exp((z - (double)mx) * invT) / S;
-      if (qp > 0.0) ratio = fmin(1.0, pt / qp);
-      else ratio = pt > 0.0 ? 1.0 : 0.0;
-      ok = u24(w[0]) < ratio;
-    } else {
-      ok = (t_j == arg);
-      pt = ok ? 1.0 : 0.0;
-      ratio = pt;
-    }
-  }
-  const unsigned long long rejected = __ballot(!ok);
-  const int n = rejected ? (int)__ffsll((long long)rejected) - 1 : m;     // first rejection, or m
-  if (lane <= k) {
-    a.out.p_tok[r0 + lane] = (float)pt;
-    a.out.ratio[r0 + lane] = (float)ratio;
-    // accepted tokens; a greedy sequence's final token is the argmax of row n, which lane n holds
-    a.out.out_tokens[r0 + lane] = (lane < n) ? t_j : ((lane == n && !(T > 0.f)) ? arg : -1);
-  }
-  int len_acc = (lane < n) ? L_j : 0;
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) len_acc += __shfl_xor(len_acc, off);
-  const int hits_acc = __popcll(__ballot(lane < n && L_j > 1));
-
-  // ---- final token at row n: its values live in lane n
-  const int fin_start = __shfl(P.start, n);
-  const int fin_L = __shfl(L_j, n);
-  const int fin_t = __shfl(t_j, n);
-  const double fin_qp = __shfl(qp, n);
-  const float fin_mx = __shfl(mx, n);
-  const double fin_S = __shfl(S, n);
-  const int fin_t_pre = __shfl(P.t_pre, n);
-  const int fin_argq = __shfl(P.argq, n);
-  const float fin_mxq = __shfl(P.mxq, n);
-  const double fin_Sq = __shfl(P.Sq, n);
-  const double fin_lq_first = __shfl(P.lq_first, n);
-  const uint32_t fin_w1 = __shfl(w[1], n);
-  if (lane == 0) {
-    a.out.n_accept[b] = n;
-    a.out.n_accept_draft[b] = len_acc;
-    a.out.hits_accepted[b] = hits_acc;
-    a.out.n_emit[b] = n + 1;
-    fin.row = r0 + n;
-    if (T > 0.f) {
-      fin.u2 = u24(fin_w1);
-      fin.mx = (double)fin_mx; fin.invT = invT; fin.invS = 1.0 / fin_S;
-      const bool unmappable = (flags & OT_FLAG_UNMAPPABLE) != 0;
-      if (n == m && !unmappable) {
-        fin.mode = 2;                                   // everything accepted: free token ~ p
-      } else {
-        fin.mode = 3;                                   // correction token ~ norm(max(0, p - q'))
-        fin.drow = q0 + fin_start;                      // the rejected span's first draft row, or the untranslatable id's
-        fin.greedy_draft = !(Td > 0.f);
-        fin.invTd = invTd;
-        fin.mxq = (double)fin_mxq;
-        fin.invSq = 1.0 / fin_Sq;
-        fin.argq = fin_argq;
-        if (n < m && fin_L > 1) {                       // Eq. 2 overrides for the n-gram matched at this position
-          fin.t_ng = fin_t;
-          fin.pi = fin_qp;
-          fin.t_pre = fin_t_pre;
-          fin.q_pre = exp(fin_lq_first) - fin_qp;
-        }
-      }
-    }
-    a.fin[b] = fin;
-  }
+  const FinalInfo fin = accept_wave(a, b, r0, k, q0, T, Td, invT, invTd, sid, P, false, 0.f, s_pmx, s_pS, s_parg, lane, true);
+  if (lane == 0) a.fin[b] = fin;
 }
 
 }  // namespace

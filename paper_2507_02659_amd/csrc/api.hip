@@ -127,9 +127,11 @@ int ot_verify_init(const ot_verify_config* cfg, ot_ctx** out) {
   }
   ok = ok && dev_alloc(c, &c->adapt_part, 2 * Bm);
   ok = ok && dev_alloc(c, &c->tile_r, Bm * c->ntiles) && dev_alloc(c, &c->tile_p, Bm * c->ntiles);
+  ok = ok && dev_alloc(c, &c->resid_count, Bm);
   if (!ok) { free_ctx(c); return fail(OT_ERR_NOMEM, "ot_verify_init: device allocation failed"); }
 
   if (c->zeros) e = hipMemsetAsync(c->zeros, 0, 64, c->stream);
+  if (e == hipSuccess) e = hipMemsetAsync(c->resid_count, 0, sizeof(int32_t) * Bm, c->stream);
   if (e == hipSuccess) e = hipMemcpyAsync(c->dmap, cfg->direct_map, sizeof(int32_t) * c->V_d, hipMemcpyHostToDevice, c->stream);
   if (e == hipSuccess) e = hipMemcpyAsync(c->tmap, tmap_h.data(), sizeof(int32_t) * c->V_t, hipMemcpyHostToDevice, c->stream);
   if (e == hipSuccess) {
@@ -193,7 +195,7 @@ static int step_impl(ot_ctx* ctx, ot_ngram_cache* cache, const ot_step_in* in, c
   a.drow_max = ctx->drow_max; a.drow_sum = ctx->drow_sum; a.drow_arg = ctx->drow_arg;
   a.fin = ctx->fin;
   a.proposal = ctx->proposal;
-  a.tile_r = ctx->tile_r; a.tile_p = ctx->tile_p;
+  a.tile_r = ctx->tile_r; a.tile_p = ctx->tile_p; a.resid_count = ctx->resid_count;
   a.out = *o;
 
   hipStream_t st = ctx->stream;
@@ -231,12 +233,10 @@ static int step_impl(ot_ctx* ctx, ot_ngram_cache* cache, const ot_step_in* in, c
   OT_MARK(1);
   if (e == hipSuccess && !a.pre_translated) e = launch_softmax_stats(a, st);
   OT_MARK(2);
-  if (e == hipSuccess) e = launch_translate_accept(a, st);
+  if (e == hipSuccess && !a.pre_translated) e = launch_translate_accept(a, st);
   OT_MARK(3);
-  if (e == hipSuccess) e = launch_resid_sums(a, st);
+  if (e == hipSuccess) e = launch_final_draw(a, st);
   OT_MARK(4);
-  if (e == hipSuccess) e = launch_resid_pick(a, st);
-  OT_MARK(5);
 #undef OT_MARK
   if (e != hipSuccess) return fail_hip(e, "ot_verify_step: launch");
   if (ev) ctx->pending += 1;

@@ -26,6 +26,7 @@ struct ot_ctx {
   otv::Partial* fpart = nullptr;      // [max_rows, Vp/256] softmax partials from the LM-head epilogue (bf16)
   otv::RowProposal* proposal = nullptr;   // [max_rows] translated proposals parked between two kernels
   double *tile_r = nullptr, *tile_p = nullptr;
+  int32_t* resid_count = nullptr;     // [max_batch] arrival counters of the residual launch, zero between launches
   otv::FinalInfo* fin = nullptr;
   void* loss_rows = nullptr;          // [max_rows] records of kLossRowBytes: per-token constants of the loss kernels
   double* loss_tiles = nullptr;       // [max_rows, ntiles] KL tile sums

@@ -134,6 +134,7 @@ struct StepArgs {
   FinalInfo* fin;        // [B]
   int32_t ntiles;        // residual tiles per row
   double* tile_r; double* tile_p;                            // [B, ntiles]
+  int32_t* resid_count;  // [B] tile workgroups of the residual launch that have delivered their mass; 0 between launches
   // outputs (device)
   ot_step_out out;
 };
@@ -155,7 +156,7 @@ hipError_t launch_lmhead_f32(const float* H, int M, int d, const float* W, float
                              hipStream_t stream);
 hipError_t launch_softmax_stats(const StepArgs& a, hipStream_t stream);
 hipError_t launch_translate_accept(const StepArgs& a, hipStream_t stream);
-hipError_t launch_resid_sums(const StepArgs& a, hipStream_t stream);
-hipError_t launch_resid_pick(const StepArgs& a, hipStream_t stream);
+// acceptance test (when the draft side ran inside the LM-head launch) and the draw of the final tokens
+hipError_t launch_final_draw(const StepArgs& a, hipStream_t stream);
 
 }  // namespace otv
