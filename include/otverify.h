@@ -241,6 +241,17 @@ typedef struct ot_adapt_out {
 } ot_adapt_out;
 int ot_adaptive_drafting(ot_ctx* ctx, const ot_adapt_in* in, ot_adapt_out* out);
 
+/* The same operation for callers that cannot allocate device memory or hold a context: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  It takes no context and allocates nothing: its only scratch
+ * (two binary64 loss partials per sequence, 64 KB) is an array inside the library's code object, one copy per GPU,
+ * held until the process ends.  Work is enqueued on `stream` (a hipStream_t, NULL = the default stream) of the current
+ * device.  Limits: B <= OT_STATIC_MAX_BATCH (else OT_ERR_SHAPE), k_b <= OT_MAX_K.  Results are identical to
+ * ot_adaptive_drafting.  All calls on one GPU share the scratch: calls whose device work overlaps on one GPU (two
+ * streams, two threads) race on it; calls on one stream do not.  The array's device address is looked up on the
+ * first call per device and by every ot_verify_init.                                                            */
+#define OT_STATIC_MAX_BATCH 4096
+int ot_adaptive_drafting_static(const ot_adapt_in* in, ot_adapt_out* out, void* stream);
+
 /* ---- diagnostics ---------------------------------------------------------------------------------------- */
 /* Device pointers into the context's workspace, valid until ot_verify_destroy and overwritten by every step.
  * Row statistics are those of the softmax of the Notation paragraph: p_j(v) = exp((z_v - row_max)/T) / row_sumexp. */

@@ -20,6 +20,7 @@ OT_ERR_NGRAM, OT_ERR_CTX_MISMATCH, OT_ERR_HIP, OT_ERR_NOMEM = -5, -6, -7, -8
 OT_BF16, OT_F32 = 0, 1
 OT_FLAG_UNMAPPABLE, OT_FLAG_RESID_ZERO, OT_FLAG_BAD_ID = 1, 2, 4
 OT_MAX_NGRAM_LEN, OT_MAX_K = 8, 63
+OT_STATIC_MAX_BATCH = 4096
 OT_N_STAGES = 4
 STAGE_NAMES = ("lm_head", "softmax_stats", "translate_accept", "residual_draw")
 
@@ -30,7 +31,7 @@ OT_NGRAM_TERM_NLL, OT_NGRAM_TERM_APPROX_KL = 0, 1
 EXPORTS = (
     "ot_verify_init", "ot_verify_destroy", "ot_ngram_cache_build", "ot_ngram_cache_create", "ot_ngram_cache_insert",
     "ot_ngram_cache_size", "ot_ngram_cache_export", "ot_ngram_cache_destroy", "ot_verify_step",
-    "ot_verify_step_from_logits", "ot_distill_loss", "ot_adaptive_drafting", "ot_verify_workspace", "ot_verify_profile",
+    "ot_verify_step_from_logits", "ot_distill_loss", "ot_adaptive_drafting", "ot_adaptive_drafting_static", "ot_verify_workspace", "ot_verify_profile",
     "ot_verify_profile_read", "ot_last_error", "ot_version",
 )
 
@@ -135,6 +136,8 @@ def load_library() -> C.CDLL:
     lib.ot_distill_loss.restype = C.c_int
     lib.ot_adaptive_drafting.argtypes = [C.c_void_p, C.POINTER(ot_adapt_in), C.POINTER(ot_adapt_out)]
     lib.ot_adaptive_drafting.restype = C.c_int
+    lib.ot_adaptive_drafting_static.argtypes = [C.POINTER(ot_adapt_in), C.POINTER(ot_adapt_out), C.c_void_p]
+    lib.ot_adaptive_drafting_static.restype = C.c_int
     lib.ot_verify_workspace.argtypes = [C.c_void_p, C.POINTER(ot_workspace_view)]
     lib.ot_verify_workspace.restype = C.c_int
     lib.ot_verify_profile.argtypes = [C.c_void_p, C.c_int32]
@@ -275,6 +278,15 @@ def ot_adaptive_drafting(ctx, *, B, gamma, w_accept=1.0, w_reject=1.0, row_off, 
                       _ptr(head_logits), _ptr(labels), _ptr(n_valid))
     aout = ot_adapt_out(_ptr(p_accept), _ptr(p_any_reject), _ptr(n_keep), _ptr(bce))
     _check(load_library().ot_adaptive_drafting(ctx, C.byref(ain), C.byref(aout)))
+
+
+def ot_adaptive_drafting_static(*, B, gamma, w_accept=1.0, w_reject=1.0, row_off, row_off_host, head_logits, labels=None,
+                                n_valid=None, p_accept, p_any_reject, n_keep, bce=None, reserved=0, stream=None):
+    """The allocation-free twin of ot_adaptive_drafting: no context, scratch inside the library, work on `stream`."""
+    ain = ot_adapt_in(int(B), float(gamma), float(w_accept), float(w_reject), int(reserved), _ptr(row_off), _ptr(row_off_host),
+                      _ptr(head_logits), _ptr(labels), _ptr(n_valid))
+    aout = ot_adapt_out(_ptr(p_accept), _ptr(p_any_reject), _ptr(n_keep), _ptr(bce))
+    _check(load_library().ot_adaptive_drafting_static(C.byref(ain), C.byref(aout), C.c_void_p(stream or 0)))
 
 
 def ot_verify_workspace(ctx) -> ot_workspace_view:

@@ -7,6 +7,8 @@
 //                       factors) so that the product has one fixed order; per-sequence loss partials go to the
 //                       workspace.
 //   adapt_total_kernel  one workgroup adds the partials in a fixed order.
+#include <mutex>
+
 #include "otv_host.h"
 
 namespace otv {
@@ -82,32 +84,81 @@ __global__ __launch_bounds__(256) void adapt_total_kernel(AdaptArgs a) {
 
 using namespace otv;
 
+namespace {
+
+// Scratch of ot_adaptive_drafting_static: the per-sequence loss partials, in an array that is part of the library's
+// code object instead of an allocation.  Every GPU the library runs on holds its own copy at its own address; that
+// address is looked up once per device (the array's name is only a host-side handle, never a device pointer).
+static __device__ __align__(256) double scratch[2 * OT_STATIC_MAX_BATCH];
+
+constexpr int kMaxDevices = 64;
+double* g_scratch_ptr[kMaxDevices];        // device address of `scratch` on each device, nullptr until looked up
+std::mutex g_scratch_mutex;
+
+// Address of `scratch` on the current device (looked up on the first call per device), or nullptr with the error set.
+double* static_scratch() {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { (void)ot_fail_hip(e, "hipGetDevice"); return nullptr; }
+  if (dev < 0 || dev >= kMaxDevices) { (void)ot_fail(OT_ERR_SHAPE, "device index %d is not supported", dev); return nullptr; }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) { (void)ot_fail_hip(e, "hipGetSymbolAddress(scratch)"); return nullptr; }
+    g_scratch_ptr[dev] = static_cast<double*>(p);
+  }
+  return g_scratch_ptr[dev];
+}
+
+// Validates the arguments shared by the two entry points and launches on `stream` with the loss partials in `part`.
+int adaptive_drafting(const char* who, const ot_adapt_in* in, ot_adapt_out* out, int max_batch, int max_k, double* part,
+                      hipStream_t stream) {
+  if (in->reserved != 0) return ot_fail(OT_ERR_SHAPE, "%s: reserved must be 0", who);
+  if (in->B < 0 || in->B > max_batch) return ot_fail(OT_ERR_SHAPE, "%s: B = %d exceeds the limit of %d sequences", who, in->B, max_batch);
+  if (!(in->gamma >= 0.f && in->gamma <= 1.f)) return ot_fail(OT_ERR_SHAPE, "%s: gamma must be in [0, 1]", who);
+  if (out->bce && !in->labels) return ot_fail(OT_ERR_NULL, "%s: the loss value needs labels", who);
+  if (out->bce && !(in->w_accept >= 0.f && in->w_reject >= 0.f)) return ot_fail(OT_ERR_SHAPE, "%s: weights must be non-negative", who);
+  AdaptArgs a{};
+  a.in = *in; a.out = *out; a.part = part;
+  if (in->B > 0) {
+    if (!in->row_off || !in->row_off_host || !in->head_logits) return ot_fail(OT_ERR_NULL, "%s: row_off, row_off_host and head_logits must not be NULL", who);
+    if (!out->p_accept || !out->p_any_reject || !out->n_keep) return ot_fail(OT_ERR_NULL, "%s: p_accept, p_any_reject and n_keep are required", who);
+    if (in->row_off_host[0] != 0) return ot_fail(OT_ERR_SHAPE, "%s: row_off[0] must be 0", who);
+    for (int b = 0; b < in->B; ++b) {
+      const int64_t rows = (int64_t)in->row_off_host[b + 1] - in->row_off_host[b];
+      if (rows < 1 || rows - 1 > max_k) return ot_fail(OT_ERR_SHAPE, "%s: sequence %d owns %lld rows", who, b, (long long)rows);
+    }
+    hipLaunchKernelGGL(adapt_rule_kernel, dim3(in->B), dim3(64), 0, stream, a);
+  }
+  if (out->bce) hipLaunchKernelGGL(adapt_total_kernel, dim3(1), dim3(256), 0, stream, a);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return ot_fail_hip(e, who);
+  return OT_OK;
+}
+
+}  // namespace
+
+// Looks up the static scratch of the current device ahead of the first ot_adaptive_drafting_static call (from
+// ot_verify_init, so that a caller who must not trigger any set-up later has it done).
+int ot_static_scratch_prepare() { return static_scratch() ? OT_OK : OT_ERR_HIP; }
+
 #pragma GCC visibility push(default)
 extern "C" {
 
 int ot_adaptive_drafting(ot_ctx* ctx, const ot_adapt_in* in, ot_adapt_out* out) {
   if (!ctx || !in || !out) return ot_fail(OT_ERR_NULL, "ot_adaptive_drafting: ctx, in and out must not be NULL");
-  if (in->reserved != 0) return ot_fail(OT_ERR_SHAPE, "ot_adaptive_drafting: reserved must be 0");
-  if (in->B < 0 || in->B > ctx->max_batch) return ot_fail(OT_ERR_SHAPE, "ot_adaptive_drafting: B = %d exceeds max_batch = %d", in->B, ctx->max_batch);
-  if (!(in->gamma >= 0.f && in->gamma <= 1.f)) return ot_fail(OT_ERR_SHAPE, "ot_adaptive_drafting: gamma must be in [0, 1]");
-  if (out->bce && !in->labels) return ot_fail(OT_ERR_NULL, "ot_adaptive_drafting: the loss value needs labels");
-  if (out->bce && !(in->w_accept >= 0.f && in->w_reject >= 0.f)) return ot_fail(OT_ERR_SHAPE, "ot_adaptive_drafting: weights must be non-negative");
-  AdaptArgs a{};
-  a.in = *in; a.out = *out; a.part = ctx->adapt_part;
-  if (in->B > 0) {
-    if (!in->row_off || !in->row_off_host || !in->head_logits) return ot_fail(OT_ERR_NULL, "ot_adaptive_drafting: row_off, row_off_host and head_logits must not be NULL");
-    if (!out->p_accept || !out->p_any_reject || !out->n_keep) return ot_fail(OT_ERR_NULL, "ot_adaptive_drafting: p_accept, p_any_reject and n_keep are required");
-    if (in->row_off_host[0] != 0) return ot_fail(OT_ERR_SHAPE, "ot_adaptive_drafting: row_off[0] must be 0");
-    for (int b = 0; b < in->B; ++b) {
-      const int64_t rows = (int64_t)in->row_off_host[b + 1] - in->row_off_host[b];
-      if (rows < 1 || rows - 1 > ctx->max_k) return ot_fail(OT_ERR_SHAPE, "ot_adaptive_drafting: sequence %d owns %lld rows", b, (long long)rows);
-    }
-    hipLaunchKernelGGL(adapt_rule_kernel, dim3(in->B), dim3(64), 0, ctx->stream, a);
-  }
-  if (out->bce) hipLaunchKernelGGL(adapt_total_kernel, dim3(1), dim3(256), 0, ctx->stream, a);
-  const hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return ot_fail_hip(e, "ot_adaptive_drafting: launch");
-  return OT_OK;
+  return adaptive_drafting("ot_adaptive_drafting", in, out, ctx->max_batch, ctx->max_k, ctx->adapt_part, ctx->stream);
+}
+
+int ot_adaptive_drafting_static(const ot_adapt_in* in, ot_adapt_out* out, void* stream) {
+  if (!in || !out) return ot_fail(OT_ERR_NULL, "ot_adaptive_drafting_static: in and out must not be NULL");
+  if (in->B > OT_STATIC_MAX_BATCH)
+    return ot_fail(OT_ERR_SHAPE, "ot_adaptive_drafting_static: B = %d exceeds OT_STATIC_MAX_BATCH = %d, the size of the static "
+                   "scratch; use ot_adaptive_drafting", in->B, OT_STATIC_MAX_BATCH);
+  double* part = static_scratch();
+  if (!part) return OT_ERR_HIP;
+  return adaptive_drafting("ot_adaptive_drafting_static", in, out, OT_STATIC_MAX_BATCH, OT_MAX_K, part, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

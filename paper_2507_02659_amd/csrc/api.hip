@@ -103,6 +103,7 @@ int ot_verify_init(const ot_verify_config* cfg, ot_ctx** out) {
   c->ntiles = ceil_div(cfg->V_t, kResidTile);
   hipError_t e = hipGetDevice(&c->device);
   if (e != hipSuccess) { free_ctx(c); return fail_hip(e, "hipGetDevice"); }
+  if (ot_static_scratch_prepare() != OT_OK) { free_ctx(c); return OT_ERR_HIP; }
 
   const size_t R = (size_t)c->max_rows, KQ = (size_t)c->max_K, Bm = (size_t)c->max_batch;
   bool ok = true;

@@ -8,6 +8,8 @@
 // Records the message ot_last_error() returns on this thread and hands back `code`.
 int ot_fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 int ot_fail_hip(hipError_t e, const char* what);
+// Looks up, for the current device, the address of the static scratch array of ot_adaptive_drafting_static.
+int ot_static_scratch_prepare();
 
 struct ot_ctx {
   int32_t d = 0, V_t = 0, V_d = 0, max_batch = 0, max_k = 0, dtype = 0, max_ngram_len = 0;
