@@ -236,7 +236,7 @@ static int step_impl(ot_ctx* ctx, ot_ngram_cache* cache, const ot_step_in* in, c
   OT_MARK(2);
   if (e == hipSuccess && !a.pre_translated) e = launch_translate_accept(a, st);
   OT_MARK(3);
-  if (e == hipSuccess) e = launch_final_draw(a, st);
+  if (e == hipSuccess) e = launch_final_draw(a, in->row_off_host, st);
   OT_MARK(4);
 #undef OT_MARK
   if (e != hipSuccess) return fail_hip(e, "ot_verify_step: launch");

@@ -157,6 +157,6 @@ hipError_t launch_lmhead_f32(const float* H, int M, int d, const float* W, float
 hipError_t launch_softmax_stats(const StepArgs& a, hipStream_t stream);
 hipError_t launch_translate_accept(const StepArgs& a, hipStream_t stream);
 // acceptance test (when the draft side ran inside the LM-head launch) and the draw of the final tokens
-hipError_t launch_final_draw(const StepArgs& a, hipStream_t stream);
+hipError_t launch_final_draw(const StepArgs& a, const int32_t* row_off_host, hipStream_t stream);
 
 }  // namespace otv

@@ -24,7 +24,15 @@ __global__ __launch_bounds__(kDrawThreads) void final_draw_kernel(StepArgs a) {
   draw_final_token(a, b, grp, f, dv, &s_draw, s_tiles);
 }
 
-__global__ __launch_bounds__(kDrawThreads) void accept_draw_kernel(StepArgs a) {
+// Row offsets of the sequences as a kernel argument (the host has them): the workgroup knows its rows without a
+// dependent load in front of everything else.
+struct RowOffsets { int32_t v[kFusedMaxB + 1]; };
+constexpr int64_t kRepeatedMergeBytes = 32 << 20;
+
+// kDraw = false: grid = (1) x (sequences); the workgroup only runs the test and leaves the outcome record in memory for
+// a final_draw_kernel launch (used when repeating the test in every tile group would cost more than a launch).
+template <bool kDraw>
+__global__ __launch_bounds__(kDrawThreads) void accept_draw_kernel(StepArgs a, RowOffsets ro) {
   const int b = blockIdx.y, grp = blockIdx.x, tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   extern __shared__ double s_tiles[];
@@ -34,16 +42,17 @@ __global__ __launch_bounds__(kDrawThreads) void accept_draw_kernel(StepArgs a) {
   __shared__ double s_pS[64];
   __shared__ int s_parg[64];
   int dv[kPerLane];
-  load_tmap<kPerLane>(a.tmap, a.V_t, draw_first_id(grp, wave, lane), 64, dv);   // needed last, asked for first
+  if (kDraw) load_tmap<kPerLane>(a.tmap, a.V_t, draw_first_id(grp, wave, lane), 64, dv);   // needed last, asked for first
 
-  const int r0 = a.row_off[b];
-  const int k = a.row_off[b + 1] - r0 - 1;
+  const int r0 = ro.v[b];
+  const int k = ro.v[b + 1] - r0 - 1;
   const float T = a.temperature[b];
   const float Td = a.draft_temperature ? a.draft_temperature[b] : T;
   const uint64_t sid = a.seq_id[b];
   const double invT = T > 0.f ? 1.0 / (double)T : 1.0;
   const double invTd = Td > 0.f ? 1.0 / (double)Td : 1.0;
   const bool lead = grp == 0;               // the group that writes the test's outputs and the row statistics
+  if (!(T > 0.f) && !lead) return;          // a greedy sequence draws nothing: its other groups have nothing to do
 
   // the proposal is parked in memory; its loads go out first so that the gather of z[t_j] follows them early and is
   // under way while the partials are merged
@@ -67,6 +76,10 @@ __global__ __launch_bounds__(kDrawThreads) void accept_draw_kernel(StepArgs a) {
                                       lane, lead);
     if (lane == 0) s_fin = fin;
   }
+  if (!kDraw) {
+    if (tid == kTestWave * 64) a.fin[b] = s_fin;
+    return;
+  }
   __syncthreads();
   const FinalInfo f = s_fin;
   if (f.mode == 0) return;
@@ -75,13 +88,26 @@ __global__ __launch_bounds__(kDrawThreads) void accept_draw_kernel(StepArgs a) {
 
 }  // namespace
 
-// pre_translated: the LM-head launch left the parked proposals and its softmax partials; otherwise a.fin is filled.
-hipError_t launch_final_draw(const StepArgs& a, hipStream_t stream) {
+// pre_translated: the LM-head launch left the parked proposals and its softmax partials (then B <= kFusedMaxB and
+// row_off_host holds the B + 1 row offsets); otherwise a.fin is filled.
+hipError_t launch_final_draw(const StepArgs& a, const int32_t* row_off_host, hipStream_t stream) {
   if (a.B == 0) return hipSuccess;
   const dim3 grid(ceil_div(a.ntiles, kGroupTiles), a.B), block(kDrawThreads);
   const size_t lds = 2 * (size_t)a.ntiles * sizeof(double);
-  if (a.pre_translated) hipLaunchKernelGGL(accept_draw_kernel, grid, block, lds, stream, a);
-  else hipLaunchKernelGGL(final_draw_kernel, grid, block, lds, stream, a);
+  if (a.pre_translated) {
+    if (a.B > kFusedMaxB) return hipErrorInvalidValue;
+    RowOffsets ro;
+    for (int b = 0; b <= kFusedMaxB; ++b) ro.v[b] = row_off_host[b <= a.B ? b : a.B];
+    // Every tile group of a sequence repeats the merge of its rows' partials: M x nfine x 16 bytes per group.  Up to
+    // about the traffic that costs as much as a launch this is one launch; beyond it the test gets a launch of its own.
+    const int64_t repeated = (int64_t)a.M * a.fused.nfine * (int64_t)sizeof(Partial) * grid.x;
+    if (repeated <= kRepeatedMergeBytes) {
+      hipLaunchKernelGGL(accept_draw_kernel<true>, grid, block, lds, stream, a, ro);
+      return hipGetLastError();
+    }
+    hipLaunchKernelGGL(accept_draw_kernel<false>, dim3(1, a.B), block, 0, stream, a, ro);
+  }
+  hipLaunchKernelGGL(final_draw_kernel, grid, block, lds, stream, a);
   return hipGetLastError();
 }
 
