@@ -6,7 +6,7 @@
  * logits and drafted ids, a direct draft->target id map and an n-gram cache (Section "Cross-vocabulary N-gram
  * Cache"), it
  *   - projects the hidden states through the LM head and forms softmax statistics of the target rows and of
- *     the draft rows (the "compute target probabilities on mapped tokens in parallel" step of Algorithm 1);
+ *     the draft rows (the parallel target pass of Algorithm 1);
  *   - translates the drafted ids into target-vocabulary tokens t_j with probabilities q'(t_j) (Eq. 1): direct
  *     id lookup, or one target token for several consecutive draft tokens that hit the cache, whose
  *     probability is the product of the sub-token probabilities;
@@ -94,8 +94,10 @@ void ot_verify_destroy(ot_ctx* ctx);          /* synchronises the stream, frees 
  *
  * Every verification step that is handed a cache advances the cache's logical clock by one and, for each entry
  * the translation scan uses (the entry becomes a mapped token of a proposal, accepted or not), adds one to the
- * entry's use count and stamps it with the clock.  Every insert call advances the clock by one and stamps the
- * entries it adds or overwrites.                                                                              */
+ * entry's use count and stamps it with the clock.  Every insert call that adds at least one pair advances the clock
+ * by one and stamps the entries it adds or overwrites (a call with n_entries == 0 changes nothing).  The cost of a
+ * maintenance call follows the number of entries it touches, not the size of the cache: the device reports the
+ * entries it used through a small log and receives the changed slots as one packed patch.                                                                             */
 #define OT_EVICT_NONE 0   /* an insert call whose new keys do not fit fails as a whole (OT_ERR_SHAPE)             */
 #define OT_EVICT_LRU  1   /* evict the entry not used for the longest time        (Appendix "N-gram Cache        */
 #define OT_EVICT_LFU  2   /* evict the entry with the fewest uses                  Scalability")                 */
@@ -105,8 +107,7 @@ int  ot_ngram_cache_build(ot_ctx* ctx, int32_t n_entries, const int32_t* key_off
                           const int32_t* target_ids, ot_ngram_cache** out);
 /* An empty cache for at most `capacity` entries (0 .. 2^26) with the given eviction policy.                    */
 int  ot_ngram_cache_create(ot_ctx* ctx, int32_t capacity, int32_t policy, ot_ngram_cache** out);
-/* Online update (Algorithm 1, "Add to n-gram cache if there exists unseen n-gram instance"): adds the pairs in
- * order.  A known key gets the new target and a fresh time stamp and keeps its use count.  A new key that finds
+/* Online update (the cache-update step that closes an iteration of Algorithm 1): adds the pairs in order.  A known key gets the new target and a fresh time stamp and keeps its use count.  A new key that finds
  * the cache full first evicts one entry: LRU the smallest (last use, insertion number), LFU the smallest (uses,
  * last use, insertion number).  *n_evicted (may be NULL) receives the number of evictions.                     */
 int  ot_ngram_cache_insert(ot_ngram_cache* cache, int32_t n_entries, const int32_t* key_off, const int32_t* key_ids,
@@ -118,6 +119,13 @@ int  ot_ngram_cache_size(const ot_ngram_cache* cache, int32_t* n_entries, int32_
  * use counts and last-use clocks [n].  OT_ERR_SHAPE if max_entries / max_key_ids are too small.                */
 int  ot_ngram_cache_export(ot_ngram_cache* cache, int32_t max_entries, int32_t max_key_ids, int32_t* key_off,
                            int32_t* key_ids, int32_t* target_ids, int64_t* uses, int64_t* last_used);
+/* Brings saved entries back with their statistics (the arrays ot_ngram_cache_export fills, all HOST, all required):
+ * the pairs are added in order like an insert, but each keeps its use count and last-use clock, nothing is evicted
+ * (OT_ERR_SHAPE if they do not fit) and the cache's clock becomes at least the largest last-use clock.  Exporting a
+ * cache and importing the result into an empty cache of the same capacity and policy therefore continues with the
+ * same eviction order as the original.  A key the cache already holds gets the given target and statistics.     */
+int  ot_ngram_cache_import(ot_ngram_cache* cache, int32_t n_entries, const int32_t* key_off, const int32_t* key_ids,
+                           const int32_t* target_ids, const int64_t* uses, const int64_t* last_used);
 void ot_ngram_cache_destroy(ot_ngram_cache* cache);
 
 /* ---- ot_verify_step ------------------------------------------------------------------------------------ */

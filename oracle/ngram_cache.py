@@ -4,21 +4,24 @@ TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).  Plain Python dictionaries, n
 
 What the paper fixes:
   * the cache is a set of pairs (target token, [draft tokens]) harvested online; after every speculative step an
-    n-gram instance that has not been seen yet is added (Algorithm 1, "Add to n-gram cache if there exists unseen
-    n-gram instance");
+    n-gram instance that has not been seen yet is added (Algorithm 1, its last step, the cache update);
   * with a maximum size, "least recently used" evicts the n-gram that has not been accessed for the longest time and
     "least frequently used" removes the n-gram with the lowest access frequency (Appendix, N-gram Cache Scalability).
 
 Readings taken where the paper is silent (mirrored by the library):
   * an *access* is a successful lookup that the translation scan actually uses (the entry becomes a mapped token of
     the proposal), whether or not the target accepts it afterwards;
-  * time is a logical clock of the cache: every verification step that uses the cache and every insert call advances
-    it by one; all entries used in one step carry that step's time; an inserted (or re-inserted) entry carries the
+  * time is a logical clock of the cache: every verification step that uses the cache and every insert call that
+    brings at least one pair advances it by one; all entries used in one step carry that step's time; an inserted (or re-inserted) entry carries the
     insert call's time;
   * victims: LRU takes the smallest (last_used, insertion number); LFU the smallest (uses, last_used, insertion
     number).  Eviction happens only when a new key arrives while the cache is full;
   * re-inserting a known key overwrites its target (the last pair wins), refreshes last_used and keeps its uses;
-  * without an eviction policy an insert call that would exceed the capacity fails as a whole.
+  * without an eviction policy an insert call that would exceed the capacity fails as a whole;
+  * an insert call without pairs changes nothing: the clock does not tick (there is no event to date);
+  * a saved cache comes back through `load`: the pairs are added in the order given, each with the use count and
+    last-use time it was saved with, nothing is evicted, and the clock moves up to the latest of those times, so
+    that an export followed by a load into an empty cache continues with the same eviction order.
 """
 from __future__ import annotations
 
@@ -84,6 +87,25 @@ class NgramCache:
             self.entries[key] = [target, 0, self.clock, self._seq]
             self._seq += 1
         return evicted
+
+    def load(self, items: Iterable[Tuple[Tuple[int, ...], int, int, int]]) -> None:
+        """Adds (key, target, uses, last_used) in order, keeping the statistics; evicts nothing."""
+        items = [(tuple(int(x) for x in k), int(t), int(u), int(l)) for k, t, u, l in items]
+        new_keys = {k for k, _, _, _ in items if k not in self.entries}
+        if len(self.entries) + len(new_keys) > self.capacity:
+            raise CacheFull(f"{len(new_keys)} saved keys do not fit into {self.capacity - len(self.entries)} free places")
+        for key, target, uses, last in items:
+            e = self.entries.get(key)
+            if e is not None:
+                e[0], e[1], e[2] = target, uses, last
+            else:
+                self.entries[key] = [target, uses, last, self._seq]
+                self._seq += 1
+            self.clock = max(self.clock, last)
+
+    def export(self) -> List[Tuple[Tuple[int, ...], int, int, int]]:
+        """(key, target, uses, last_used) in insertion order."""
+        return [(k, v[0], v[1], v[2]) for k, v in sorted(self.entries.items(), key=lambda kv: kv[1][3])]
 
     def record_step(self, used_keys: Iterable[Tuple[int, ...]]) -> None:
         """One verification step used these keys (with multiplicity)."""

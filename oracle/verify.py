@@ -7,7 +7,7 @@ no code with the HIP path and the product never calls it.
 What it computes (OmniDraft, Methodology): for every sequence of a batch,
 
   1. target logits z_j = h_j . W for the k+1 verified rows (Algorithm 1, the
-     "compute target probabilities on mapped tokens in parallel" step) and the
+     parallel target pass over the mapped tokens) and the
      target distribution p_j = softmax(z_j / T)              (Notation paragraph);
   2. the draft distribution q_i = softmax(zq_i / T_d) at each drafted position;
   3. the translation of the drafted ids d_0..d_{k-1} into target-vocabulary

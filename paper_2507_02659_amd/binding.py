@@ -30,7 +30,7 @@ OT_NGRAM_TERM_NLL, OT_NGRAM_TERM_APPROX_KL = 0, 1
 
 EXPORTS = (
     "ot_verify_init", "ot_verify_destroy", "ot_ngram_cache_build", "ot_ngram_cache_create", "ot_ngram_cache_insert",
-    "ot_ngram_cache_size", "ot_ngram_cache_export", "ot_ngram_cache_destroy", "ot_verify_step",
+    "ot_ngram_cache_size", "ot_ngram_cache_export", "ot_ngram_cache_import", "ot_ngram_cache_destroy", "ot_verify_step",
     "ot_verify_step_from_logits", "ot_distill_loss", "ot_adaptive_drafting", "ot_adaptive_drafting_static", "ot_verify_workspace", "ot_verify_profile",
     "ot_verify_profile_read", "ot_last_error", "ot_version",
 )
@@ -127,6 +127,8 @@ def load_library() -> C.CDLL:
     lib.ot_ngram_cache_export.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.c_void_p, C.c_void_p]
     lib.ot_ngram_cache_export.restype = C.c_int
+    lib.ot_ngram_cache_import.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.ot_ngram_cache_import.restype = C.c_int
     lib.ot_verify_step.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(ot_step_in), C.POINTER(ot_step_out)]
     lib.ot_verify_step.restype = C.c_int
     lib.ot_verify_step_from_logits.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(ot_step_in), C.c_void_p, C.POINTER(ot_step_out)]
@@ -221,6 +223,16 @@ def ot_ngram_cache_insert(cache, key_off, key_ids, target_ids) -> int:
     ev = C.c_int32()
     _check(load_library().ot_ngram_cache_insert(cache, int(ti.size), _ptr(ko), _ptr(ki), _ptr(ti), C.byref(ev)))
     return int(ev.value)
+
+
+def ot_ngram_cache_import(cache, key_off, key_ids, target_ids, uses, last_used) -> None:
+    """Brings saved entries back with their statistics (the arrays ot_ngram_cache_export returns)."""
+    ko = np.ascontiguousarray(key_off, dtype=np.int32)
+    ki = np.ascontiguousarray(key_ids, dtype=np.int32)
+    ti = np.ascontiguousarray(target_ids, dtype=np.int32)
+    us = np.ascontiguousarray(uses, dtype=np.int64)
+    lu = np.ascontiguousarray(last_used, dtype=np.int64)
+    _check(load_library().ot_ngram_cache_import(cache, int(ti.size), _ptr(ko), _ptr(ki), _ptr(ti), _ptr(us), _ptr(lu)))
 
 
 def ot_ngram_cache_size(cache):

@@ -16,7 +16,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OUT_DIR = os.path.join(PKG, "_build")
 LIB_PATH = os.path.join(PKG, "libotverify.so")
-SOURCES = ["api.hip", "cache.hip", "lmhead.hip", "stats.hip", "accept.hip", "resid.hip", "loss.hip", "adapt.hip"]
+SOURCES = ["api.hip", "cache.hip", "ngram_table.cpp", "lmhead.hip", "stats.hip", "accept.hip", "resid.hip", "loss.hip", "adapt.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -29,7 +29,7 @@ FLAGS = [
 
 
 def _compile(src: str) -> str:
-    obj = os.path.join(OUT_DIR, src.replace(".hip", ".o"))
+    obj = os.path.join(OUT_DIR, os.path.splitext(src)[0] + ".o")
     cmd = [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:

@@ -161,11 +161,10 @@ static int step_impl(ot_ctx* ctx, ot_ngram_cache* cache, const ot_step_in* in, c
   if (in->B == 0) return OT_OK;
   if (!in->row_off || !in->row_off_host || !in->temperature || !in->seq_id)
     return fail(OT_ERR_NULL, "ot_verify_step: row_off, row_off_host, temperature and seq_id must not be NULL");
-  if (in->row_off_host[0] != 0) return fail(OT_ERR_SHAPE, "ot_verify_step: row_off[0] must be 0");
-  for (int b = 0; b < in->B; ++b) {
-    const int64_t rows = (int64_t)in->row_off_host[b + 1] - in->row_off_host[b];
-    if (rows < 1) return fail(OT_ERR_SHAPE, "ot_verify_step: sequence %d has %lld rows; every sequence owns k_b + 1 >= 1 rows", b, (long long)rows);
-    if (rows - 1 > ctx->max_k) return fail(OT_ERR_SHAPE, "ot_verify_step: sequence %d drafted %lld tokens, max_k = %d", b, (long long)(rows - 1), ctx->max_k);
+  {
+    const char* what = "";
+    const int bad = check_row_offsets(in->B, in->row_off_host, ctx->max_k, &what);
+    if (bad) return fail(OT_ERR_SHAPE, "ot_verify_step: sequence %d: %s (max_k = %d)", bad - 1, what, ctx->max_k);
   }
   const int M = in->row_off_host[in->B], K = M - in->B;
   if (from_logits ? !ext_logits : !in->hidden) return fail(OT_ERR_NULL, "ot_verify_step: %s must not be NULL", from_logits ? "target_logits" : "hidden");
@@ -181,11 +180,11 @@ static int step_impl(ot_ctx* ctx, ot_ngram_cache* cache, const ot_step_in* in, c
   a.row_off = in->row_off; a.hidden = in->hidden; a.draft_logits = in->draft_logits; a.draft_ids = in->draft_ids;
   a.temperature = in->temperature; a.draft_temperature = in->draft_temperature; a.seq_id = in->seq_id;
   a.dmap = ctx->dmap; a.tmap = ctx->tmap;
-  if (cache) cache->clock += 1;             // one tick of the cache's logical time per step that is given the cache
-  if (cache && cache->n_entries > 0) {
-    a.cache.slots = cache->d_slots; a.cache.mask = cache->mask; a.cache.stride = cache->stride;
-    a.cache.max_len = cache->max_len; a.cache.uses = cache->d_uses; a.cache.last_used = cache->d_last;
-    a.cache.clock = cache->clock;
+  if (cache) cache->tab.tick();             // one tick of the cache's logical time per step that is given the cache
+  if (cache && cache->tab.size() > 0) {
+    a.cache.slots = cache->d_slots; a.cache.mask = cache->tab.mask(); a.cache.stride = cache->tab.stride();
+    a.cache.max_len = cache->tab.max_len(); a.cache.uses = cache->d_uses; a.cache.last_used = cache->d_last;
+    a.cache.clock = cache->tab.clock(); a.cache.log = cache->d_log;
   }
   a.Z = from_logits ? ext_logits : ctx->Z;
   a.ldz = ctx->V_t;

@@ -1,15 +1,19 @@
-// Host side of the n-gram cache C = {(t_i, [d_j])} (Section "Cross-vocabulary N-gram Cache"): bulk build, online
-// insertion (Algorithm 1, "Add to n-gram cache if there exists unseen n-gram instance"), eviction at a maximum size
-// (Appendix "N-gram Cache Scalability": least recently used / least frequently used) and export.
+// Device side of the n-gram cache C = {(t_i, [d_j])} (Section "Cross-vocabulary N-gram Cache") and the entry points
+// that maintain it: bulk build, online insertion (the cache-update step at the end of Algorithm 1), eviction at a
+// maximum size (Appendix "N-gram Cache Scalability": least recently used / least frequently used), export and import.
 //
-// The table is open addressing with linear probing, mirrored on the host; the device copy is what the translation
-// kernel probes, and the kernel keeps two counters per slot (uses, last use).  All maintenance happens between
-// steps: every call here first synchronises the context's stream.  Deletion is backward-shift deletion, so the
-// table never holds tombstones and a probe still ends at the first empty slot.
+// The table itself, its use statistics and the eviction order live on the host in plain C++ (ngram_table.h); the
+// device holds a copy that the translation kernel probes.  The two are kept in step incrementally:
+//   device -> host  the translation kernel appends (slot, clock) to a small log for every entry it uses; a maintenance
+//                   call reads the log (a few words) and replays it on the host table.  A log that overflowed is
+//                   replaced by a read-back of the per-slot counters.
+//   host -> device  the host records the slots it changed; they travel as one packed patch (one copy, one small
+//                   kernel that also clears the log).  Only a change of more than kPatchCap slots (a bulk build)
+//                   uploads the arrays whole.
+// All maintenance happens between steps: every call here first synchronises the context's stream.
 #include <algorithm>
 #include <cstring>
 #include <new>
-#include <set>
 
 #include "otv_host.h"
 
@@ -19,91 +23,102 @@ namespace {
 
 constexpr int32_t kMaxCapacity = 1 << 26;    // slot indices must fit in 28 bits next to the key length
 
-inline int32_t* slot_of(ot_ngram_cache* c, uint32_t s) { return &c->table[(size_t)s * c->stride]; }
-
-// Slot that holds `ids`, or the empty slot where it would go.
-uint32_t find_slot(ot_ngram_cache* c, const int32_t* ids, int len, bool* found) {
-  uint32_t h = hash_ngram(ids, len) & c->mask;
-  for (;;) {
-    const int32_t* s = slot_of(c, h);
-    if (s[0] == 0) { *found = false; return h; }
-    if (s[0] == len && std::memcmp(s + 2, ids, sizeof(int32_t) * len) == 0) { *found = true; return h; }
-    h = (h + 1) & c->mask;
-  }
+// Scatters a packed patch into the device table.  Record r = { slot, uses, last_used, slot words[stride] }.
+__global__ __launch_bounds__(256) void cache_patch_kernel(const uint32_t* __restrict__ patch, int n, int stride,
+                                                          int32_t* __restrict__ slots, uint32_t* __restrict__ uses,
+                                                          uint32_t* __restrict__ last, uint32_t* __restrict__ log) {
+  const int words = 3 + stride;
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i == 0) log[0] = 0;                    // the log has been read: start it over
+  if (i >= n * words) return;
+  const int r = i / words, w = i % words;
+  const uint32_t* rec = patch + (size_t)r * words;
+  const uint32_t s = rec[0];
+  if (w == 1) uses[s] = rec[1];
+  else if (w == 2) last[s] = rec[2];
+  else if (w >= 3) slots[(size_t)s * stride + (w - 3)] = (int32_t)rec[w];
 }
 
-struct Counters {                 // host copies of the device counters, fetched only when a call needs them
-  std::vector<uint32_t> uses, last;
-  bool loaded = false;
-};
-
-int load_counters(ot_ngram_cache* c, Counters* k) {
-  if (k->loaded) return OT_OK;
-  const size_t n = (size_t)c->mask + 1;
-  try { k->uses.resize(n); k->last.resize(n); } catch (const std::bad_alloc&) { return ot_fail(OT_ERR_NOMEM, "n-gram cache: host allocation failed"); }
-  hipError_t e = hipMemcpy(k->uses.data(), c->d_uses, n * sizeof(uint32_t), hipMemcpyDeviceToHost);
-  if (e == hipSuccess) e = hipMemcpy(k->last.data(), c->d_last, n * sizeof(uint32_t), hipMemcpyDeviceToHost);
-  if (e != hipSuccess) return ot_fail_hip(e, "n-gram cache: reading the use counters");
-  k->loaded = true;
+// Replays what the device did since the last maintenance call on the host table.  The stream has been synchronised.
+int pull_use_log(ot_ngram_cache* c) {
+  uint32_t* h = c->h_stage;
+  const size_t first = 1 + 2 * (size_t)kCacheLogFirst;
+  hipError_t e = hipMemcpy(h, c->d_log, first * sizeof(uint32_t), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return ot_fail_hip(e, "n-gram cache: reading the use log");
+  const uint32_t count = h[0];
+  c->log_pending = count != 0;
+  if (count > (uint32_t)kCacheLogCap) {
+    // more uses than the log holds: take the per-slot counters instead
+    const size_t n = c->tab.slots();
+    std::vector<uint32_t> uses, last;
+    try { uses.resize(n); last.resize(n); } catch (const std::bad_alloc&) { return ot_fail(OT_ERR_NOMEM, "n-gram cache: host allocation failed"); }
+    e = hipMemcpy(uses.data(), c->d_uses, n * sizeof(uint32_t), hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(last.data(), c->d_last, n * sizeof(uint32_t), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return ot_fail_hip(e, "n-gram cache: reading the use counters");
+    c->tab.replace_statistics(uses.data(), last.data());
+    return OT_OK;
+  }
+  if (count > (uint32_t)kCacheLogFirst) {
+    e = hipMemcpy(h + first, c->d_log + first, 2 * (size_t)(count - kCacheLogFirst) * sizeof(uint32_t), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return ot_fail_hip(e, "n-gram cache: reading the use log");
+  }
+  for (uint32_t i = 0; i < count; ++i) {
+    if (!c->tab.record_use(h[1 + 2 * i], h[2 + 2 * i])) return ot_fail(OT_ERR_HIP, "n-gram cache: the use log names an empty slot");
+  }
   return OT_OK;
 }
 
-// Removes the entry in slot i and closes the gap (backward-shift deletion for linear probing).
-void erase_slot(ot_ngram_cache* c, Counters* k, uint32_t i) {
-  const uint32_t mask = c->mask;
-  uint32_t j = i;
-  for (;;) {
-    slot_of(c, i)[0] = 0;
-    for (;;) {
-      j = (j + 1) & mask;
-      int32_t* sj = slot_of(c, j);
-      if (sj[0] == 0) {                      // the gap stays at i: an empty slot carries no statistics
-        k->uses[i] = 0; k->last[i] = 0; c->seq[i] = 0;
-        return;
-      }
-      const uint32_t home = hash_ngram(sj + 2, sj[0]) & mask;
-      // the entry at j may stay if its home slot lies cyclically in (i, j]
-      const bool stays = (i <= j) ? (i < home && home <= j) : (i < home || home <= j);
-      if (!stays) break;
-    }
-    std::memcpy(slot_of(c, i), slot_of(c, j), sizeof(int32_t) * c->stride);
-    k->uses[i] = k->uses[j]; k->last[i] = k->last[j]; c->seq[i] = c->seq[j];
-    i = j;
+// Sends the slots the host changed to the device (asynchronously on the context's stream) and clears the device log.
+int push_changes(ot_ngram_cache* c) {
+  std::vector<uint32_t> dirty = c->tab.take_dirty();
+  hipStream_t st = c->owner->stream;
+  const int stride = c->tab.stride();
+  hipError_t e = hipSuccess;
+  if ((int64_t)dirty.size() > kCachePatchCap) {
+    const size_t n = c->tab.slots();
+    e = hipMemcpy(c->d_slots, c->tab.table().data(), c->tab.table().size() * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(c->d_uses, c->tab.all_uses().data(), n * sizeof(uint32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(c->d_last, c->tab.all_last_used().data(), n * sizeof(uint32_t), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return ot_fail_hip(e, "n-gram cache: upload");
+    dirty.clear();
   }
-}
-
-uint32_t pick_victim(ot_ngram_cache* c, const Counters& k) {
-  uint32_t best = 0;
-  bool have = false;
-  for (uint32_t s = 0; s <= c->mask; ++s) {
-    if (slot_of(c, s)[0] == 0) continue;
-    bool better;
-    if (!have) better = true;
-    else if (c->policy == OT_EVICT_LRU)
-      better = k.last[s] != k.last[best] ? k.last[s] < k.last[best] : c->seq[s] < c->seq[best];
-    else
-      better = k.uses[s] != k.uses[best] ? k.uses[s] < k.uses[best]
-             : k.last[s] != k.last[best] ? k.last[s] < k.last[best] : c->seq[s] < c->seq[best];
-    if (better) { best = s; have = true; }
+  if (dirty.empty() && !c->log_pending) return OT_OK;
+  const int words = 3 + stride;
+  uint32_t* h = c->h_stage;
+  for (size_t r = 0; r < dirty.size(); ++r) {
+    const uint32_t s = dirty[r];
+    uint32_t* rec = h + r * words;
+    rec[0] = s; rec[1] = c->tab.uses(s); rec[2] = c->tab.last_used(s);
+    std::memcpy(rec + 3, c->tab.slot(s), sizeof(int32_t) * stride);
   }
-  return best;
+  const int n = (int)dirty.size();
+  if (n > 0) e = hipMemcpyAsync(c->d_patch, h, (size_t)n * words * sizeof(uint32_t), hipMemcpyHostToDevice, st);
+  if (e != hipSuccess) return ot_fail_hip(e, "n-gram cache: patch upload");
+  hipLaunchKernelGGL(cache_patch_kernel, dim3(std::max(1, ceil_div((int64_t)n * words, 256))), dim3(256), 0, st, c->d_patch, n,
+                     stride, c->d_slots, c->d_uses, c->d_last, c->d_log);
+  e = hipGetLastError();
+  if (e != hipSuccess) return ot_fail_hip(e, "n-gram cache: patch launch");
+  c->log_pending = false;
+  return OT_OK;
 }
 
 int validate_entries(ot_ctx* ctx, const char* who, int32_t n, const int32_t* key_off, const int32_t* key_ids,
                      const int32_t* target_ids) {
   if (n < 0) return ot_fail(OT_ERR_SHAPE, "%s: n_entries < 0", who);
   if (n > 0 && (!key_off || !key_ids || !target_ids)) return ot_fail(OT_ERR_NULL, "%s: NULL entry arrays", who);
-  for (int32_t e = 0; e < n; ++e) {
-    const int64_t len = (int64_t)key_off[e + 1] - key_off[e];
-    if (key_off[e] < 0 || len < 2 || len > ctx->max_ngram_len)
-      return ot_fail(OT_ERR_NGRAM, "%s: entry %d has length %lld, allowed 2..%d", who, e, (long long)len, ctx->max_ngram_len);
-    for (int64_t i = key_off[e]; i < key_off[e + 1]; ++i)
-      if (key_ids[i] < 0 || key_ids[i] >= ctx->V_d)
-        return ot_fail(OT_ERR_NGRAM, "%s: entry %d holds draft id %d outside [0, V_d)", who, e, key_ids[i]);
-    if (target_ids[e] < 0 || target_ids[e] >= ctx->V_t)
-      return ot_fail(OT_ERR_NGRAM, "%s: entry %d maps to target id %d outside [0, V_t)", who, e, target_ids[e]);
-  }
+  const char* what = "";
+  const int bad = check_entries(n, key_off, key_ids, target_ids, ctx->max_ngram_len, ctx->V_d, ctx->V_t, &what);
+  if (bad) return ot_fail(OT_ERR_NGRAM, "%s: entry %d: %s (V_d = %d, V_t = %d, max_ngram_len = %d)", who, bad - 1, what, ctx->V_d,
+                          ctx->V_t, ctx->max_ngram_len);
   return OT_OK;
+}
+
+// Start of every maintenance call: no step may be probing the table while it changes, and the host table first
+// catches up with what the device did.
+int begin_maintenance(ot_ngram_cache* c, const char* who) {
+  hipError_t he = hipStreamSynchronize(c->owner->stream);
+  if (he != hipSuccess) return ot_fail_hip(he, who);
+  return pull_use_log(c);
 }
 
 }  // namespace
@@ -119,28 +134,30 @@ int ot_ngram_cache_create(ot_ctx* ctx, int32_t capacity, int32_t policy, ot_ngra
     return ot_fail(OT_ERR_SHAPE, "ot_ngram_cache_create: unknown eviction policy %d", policy);
   ot_ngram_cache* c = new (std::nothrow) ot_ngram_cache();
   if (!c) return ot_fail(OT_ERR_NOMEM, "ot_ngram_cache_create: host allocation failed");
-  uint32_t slots = 16;
-  while (slots < 2u * (uint32_t)capacity) slots <<= 1;
-  c->owner = ctx; c->capacity = capacity; c->policy = policy; c->stride = 2 + ctx->max_ngram_len;
-  c->max_len = ctx->max_ngram_len; c->mask = slots - 1;
+  c->owner = ctx;
   try {
-    c->table.assign((size_t)slots * c->stride, 0);
-    c->seq.assign(slots, 0);
+    c->tab.init(capacity, policy, ctx->max_ngram_len);
   } catch (const std::bad_alloc&) {
     delete c;
     return ot_fail(OT_ERR_NOMEM, "ot_ngram_cache_create: host allocation failed");
   }
-  hipError_t e = hipMalloc(reinterpret_cast<void**>(&c->d_slots), c->table.size() * sizeof(int32_t));
+  const size_t slots = c->tab.slots(), words = c->tab.table().size();
+  const size_t stage_words = std::max<size_t>(1 + 2 * (size_t)kCacheLogCap, (size_t)kCachePatchCap * (3 + c->tab.stride()));
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&c->d_slots), words * sizeof(int32_t));
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->d_uses), slots * sizeof(uint32_t));
   if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->d_last), slots * sizeof(uint32_t));
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->d_log), (1 + 2 * (size_t)kCacheLogCap) * sizeof(uint32_t));
+  if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->d_patch), stage_words * sizeof(uint32_t));
+  if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void**>(&c->h_stage), stage_words * sizeof(uint32_t), hipHostMallocDefault);
   if (e != hipSuccess) {
     (void)hipGetLastError();
     ot_ngram_cache_destroy(c);
-    return ot_fail(OT_ERR_NOMEM, "ot_ngram_cache_create: device allocation failed");
+    return ot_fail(OT_ERR_NOMEM, "ot_ngram_cache_create: allocation failed");
   }
-  e = hipMemset(c->d_slots, 0, c->table.size() * sizeof(int32_t));
+  e = hipMemset(c->d_slots, 0, words * sizeof(int32_t));
   if (e == hipSuccess) e = hipMemset(c->d_uses, 0, slots * sizeof(uint32_t));
   if (e == hipSuccess) e = hipMemset(c->d_last, 0, slots * sizeof(uint32_t));
+  if (e == hipSuccess) e = hipMemset(c->d_log, 0, sizeof(uint32_t));
   if (e != hipSuccess) { ot_ngram_cache_destroy(c); return ot_fail_hip(e, "ot_ngram_cache_create: clearing the table"); }
   *out = c;
   return OT_OK;
@@ -152,73 +169,46 @@ int ot_ngram_cache_insert(ot_ngram_cache* c, int32_t n_entries, const int32_t* k
   if (!c) return ot_fail(OT_ERR_NULL, "ot_ngram_cache_insert: cache is NULL");
   int rc = validate_entries(c->owner, "ot_ngram_cache_insert", n_entries, key_off, key_ids, target_ids);
   if (rc != OT_OK) return rc;
-  if (n_entries == 0) return OT_OK;
+  if (n_entries == 0) return OT_OK;                            // nothing to add: not even a tick of the clock
 
-  // how many places do the new keys of this call need?
-  bool found;
-  int64_t fresh = 0;
-  {
-    std::set<std::vector<int32_t>> seen;
-    for (int32_t e = 0; e < n_entries; ++e) {
-      const int32_t* ids = key_ids + key_off[e];
-      const int len = key_off[e + 1] - key_off[e];
-      find_slot(c, ids, len, &found);
-      if (!found && seen.insert(std::vector<int32_t>(ids, ids + len)).second) ++fresh;
-    }
-  }
-  const bool overflow = (int64_t)c->n_entries + fresh > c->capacity;
-  if (overflow && (c->policy == OT_EVICT_NONE || c->capacity == 0))
+  const int64_t fresh = c->tab.count_fresh(n_entries, key_off, key_ids);
+  const bool overflow = (int64_t)c->tab.size() + fresh > c->tab.capacity();
+  if (overflow && (c->tab.policy() == OT_EVICT_NONE || c->tab.capacity() == 0))
     return ot_fail(OT_ERR_SHAPE, "ot_ngram_cache_insert: %lld new keys do not fit into %d free places and the cache has no "
-                   "eviction policy", (long long)fresh, c->capacity - c->n_entries);
-
-  hipError_t he = hipStreamSynchronize(c->owner->stream);      // no step may be probing the table while it changes
-  if (he != hipSuccess) return ot_fail_hip(he, "ot_ngram_cache_insert: synchronize");
-
-  Counters k;
-  const bool bulk = overflow || n_entries > 32;                // bulk: work on full host copies, upload everything
-  if (bulk && (rc = load_counters(c, &k)) != OT_OK) return rc;
-  c->clock += 1;
-  std::vector<uint32_t> touched;
+                   "eviction policy", (long long)fresh, c->tab.capacity() - c->tab.size());
+  if ((rc = begin_maintenance(c, "ot_ngram_cache_insert: synchronize")) != OT_OK) return rc;
   int32_t evicted = 0;
-  for (int32_t e = 0; e < n_entries; ++e) {
-    const int32_t* ids = key_ids + key_off[e];
-    const int len = key_off[e + 1] - key_off[e];
-    uint32_t s = find_slot(c, ids, len, &found);
-    if (!found) {
-      if (c->n_entries >= c->capacity) {                       // full: make room (only reachable in bulk mode)
-        erase_slot(c, &k, pick_victim(c, k));
-        c->n_entries -= 1;
-        ++evicted;
-        s = find_slot(c, ids, len, &found);                    // the shift may have moved the insertion point
-      }
-      int32_t* slot = slot_of(c, s);
-      slot[0] = len;
-      std::memcpy(slot + 2, ids, sizeof(int32_t) * len);
-      std::fill(slot + 2 + len, slot + c->stride, 0);
-      c->seq[s] = c->next_seq++;
-      c->n_entries += 1;
-      if (bulk) k.uses[s] = 0;
-    }
-    slot_of(c, s)[1] = target_ids[e];                          // equal key: the later pair wins
-    if (bulk) k.last[s] = c->clock;
-    else touched.push_back(s);
+  try {
+    evicted = c->tab.insert(n_entries, key_off, key_ids, target_ids);
+  } catch (const std::bad_alloc&) {
+    return ot_fail(OT_ERR_NOMEM, "ot_ngram_cache_insert: host allocation failed");
   }
-  if (bulk) {
-    const size_t n = (size_t)c->mask + 1;
-    he = hipMemcpy(c->d_slots, c->table.data(), c->table.size() * sizeof(int32_t), hipMemcpyHostToDevice);
-    if (he == hipSuccess) he = hipMemcpy(c->d_uses, k.uses.data(), n * sizeof(uint32_t), hipMemcpyHostToDevice);
-    if (he == hipSuccess) he = hipMemcpy(c->d_last, k.last.data(), n * sizeof(uint32_t), hipMemcpyHostToDevice);
-  } else {
-    // a few slots changed and nothing moved: patch them in place (a fresh slot's use counter is still 0 on the device)
-    for (uint32_t s : touched) {
-      if (he == hipSuccess)
-        he = hipMemcpy(c->d_slots + (size_t)s * c->stride, slot_of(c, s), sizeof(int32_t) * c->stride, hipMemcpyHostToDevice);
-      if (he == hipSuccess) he = hipMemcpy(c->d_last + s, &c->clock, sizeof(uint32_t), hipMemcpyHostToDevice);
-    }
-  }
-  if (he != hipSuccess) return ot_fail_hip(he, "ot_ngram_cache_insert: upload");
+  if ((rc = push_changes(c)) != OT_OK) return rc;
   if (n_evicted) *n_evicted = evicted;
   return OT_OK;
+}
+
+int ot_ngram_cache_import(ot_ngram_cache* c, int32_t n_entries, const int32_t* key_off, const int32_t* key_ids,
+                          const int32_t* target_ids, const int64_t* uses, const int64_t* last_used) {
+  if (!c) return ot_fail(OT_ERR_NULL, "ot_ngram_cache_import: cache is NULL");
+  int rc = validate_entries(c->owner, "ot_ngram_cache_import", n_entries, key_off, key_ids, target_ids);
+  if (rc != OT_OK) return rc;
+  if (n_entries == 0) return OT_OK;
+  if (!uses || !last_used) return ot_fail(OT_ERR_NULL, "ot_ngram_cache_import: uses and last_used must not be NULL");
+  for (int32_t e = 0; e < n_entries; ++e)
+    if (uses[e] < 0 || uses[e] > 0xFFFFFFFFll || last_used[e] < 0 || last_used[e] > 0xFFFFFFFFll)
+      return ot_fail(OT_ERR_SHAPE, "ot_ngram_cache_import: entry %d carries statistics outside 0..2^32-1", e);
+  const int64_t fresh = c->tab.count_fresh(n_entries, key_off, key_ids);
+  if ((int64_t)c->tab.size() + fresh > c->tab.capacity())
+    return ot_fail(OT_ERR_SHAPE, "ot_ngram_cache_import: %lld new keys do not fit into %d free places (an import evicts nothing)",
+                   (long long)fresh, c->tab.capacity() - c->tab.size());
+  if ((rc = begin_maintenance(c, "ot_ngram_cache_import: synchronize")) != OT_OK) return rc;
+  try {
+    c->tab.import_entries(n_entries, key_off, key_ids, target_ids, uses, last_used);
+  } catch (const std::bad_alloc&) {
+    return ot_fail(OT_ERR_NOMEM, "ot_ngram_cache_import: host allocation failed");
+  }
+  return push_changes(c);
 }
 
 int ot_ngram_cache_build(ot_ctx* ctx, int32_t n_entries, const int32_t* key_off, const int32_t* key_ids,
@@ -239,42 +229,20 @@ int ot_ngram_cache_build(ot_ctx* ctx, int32_t n_entries, const int32_t* key_off,
 
 int ot_ngram_cache_size(const ot_ngram_cache* c, int32_t* n_entries, int32_t* n_key_ids) {
   if (!c || !n_entries) return ot_fail(OT_ERR_NULL, "ot_ngram_cache_size: NULL argument");
-  *n_entries = c->n_entries;
-  if (n_key_ids) {
-    int64_t ids = 0;
-    for (uint32_t s = 0; s <= c->mask; ++s) ids += c->table[(size_t)s * c->stride];
-    *n_key_ids = (int32_t)ids;
-  }
+  *n_entries = c->tab.size();
+  if (n_key_ids) *n_key_ids = (int32_t)c->tab.total_key_ids();
   return OT_OK;
 }
 
 int ot_ngram_cache_export(ot_ngram_cache* c, int32_t max_entries, int32_t max_key_ids, int32_t* key_off,
                           int32_t* key_ids, int32_t* target_ids, int64_t* uses, int64_t* last_used) {
   if (!c || !key_off || !key_ids || !target_ids) return ot_fail(OT_ERR_NULL, "ot_ngram_cache_export: NULL argument");
-  hipError_t he = hipStreamSynchronize(c->owner->stream);
-  if (he != hipSuccess) return ot_fail_hip(he, "ot_ngram_cache_export: synchronize");
-  Counters k;
-  int rc = load_counters(c, &k);
+  int rc = begin_maintenance(c, "ot_ngram_cache_export: synchronize");
   if (rc != OT_OK) return rc;
-  if (max_entries < c->n_entries) return ot_fail(OT_ERR_SHAPE, "ot_ngram_cache_export: room for %d entries, cache holds %d", max_entries, c->n_entries);
-  // entries leave in insertion order, so that re-inserting an export reproduces the tie-breaking of the original
-  std::vector<uint32_t> order;
-  for (uint32_t s = 0; s <= c->mask; ++s) if (slot_of(c, s)[0] != 0) order.push_back(s);
-  std::sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return c->seq[a] < c->seq[b]; });
-  int64_t at = 0;
-  int32_t e = 0;
-  key_off[0] = 0;
-  for (uint32_t s : order) {
-    const int32_t* slot = slot_of(c, s);
-    if (at + slot[0] > max_key_ids) return ot_fail(OT_ERR_SHAPE, "ot_ngram_cache_export: room for %d key ids is not enough", max_key_ids);
-    std::memcpy(key_ids + at, slot + 2, sizeof(int32_t) * slot[0]);
-    at += slot[0];
-    target_ids[e] = slot[1];
-    if (uses) uses[e] = k.uses[s];
-    if (last_used) last_used[e] = k.last[s];
-    key_off[++e] = (int32_t)at;
-  }
-  return OT_OK;
+  if (max_entries < c->tab.size()) return ot_fail(OT_ERR_SHAPE, "ot_ngram_cache_export: room for %d entries, cache holds %d", max_entries, c->tab.size());
+  if (max_key_ids < c->tab.total_key_ids()) return ot_fail(OT_ERR_SHAPE, "ot_ngram_cache_export: room for %d key ids is not enough", max_key_ids);
+  c->tab.export_entries(key_off, key_ids, target_ids, uses, last_used);
+  return push_changes(c);        // nothing changed on the host; clears the device log that was just replayed
 }
 
 void ot_ngram_cache_destroy(ot_ngram_cache* cache) {
@@ -283,6 +251,9 @@ void ot_ngram_cache_destroy(ot_ngram_cache* cache) {
   if (cache->d_slots) (void)hipFree(cache->d_slots);
   if (cache->d_uses) (void)hipFree(cache->d_uses);
   if (cache->d_last) (void)hipFree(cache->d_last);
+  if (cache->d_log) (void)hipFree(cache->d_log);
+  if (cache->d_patch) (void)hipFree(cache->d_patch);
+  if (cache->h_stage) (void)hipHostFree(cache->h_stage);
   delete cache;
 }
 

@@ -3,6 +3,7 @@
 
 #include <vector>
 
+#include "ngram_table.h"
 #include "otv_internal.h"
 
 // Records the message ot_last_error() returns on this thread and hands back `code`.
@@ -39,20 +40,16 @@ struct ot_ctx {
   int pending = 0;
 };
 
-// One n-gram cache: an open-addressing table (linear probing) mirrored on the host, plus per-slot use statistics
-// that the translation kernel updates on the device.
+// One n-gram cache: the host table with its statistics and eviction order (plain C++), and the device copy that the
+// translation kernel probes.
 struct ot_ngram_cache {
   ot_ctx* owner = nullptr;
-  int32_t capacity = 0;               // most entries the cache may hold
-  int32_t policy = OT_EVICT_NONE;
-  int32_t n_entries = 0;
-  int32_t stride = 0, max_len = 0;    // int32 words per slot, longest key
-  uint32_t mask = 0;                  // slots - 1
-  uint32_t clock = 0;                 // logical time: +1 per step that uses the cache and per insert call
-  uint64_t next_seq = 0;              // insertion numbers
-  std::vector<int32_t> table;         // host mirror of the slots
-  std::vector<uint64_t> seq;          // host only: insertion number of the entry in each slot
-  int32_t* d_slots = nullptr;         // device copies
+  otv::NgramTable tab;
+  int32_t* d_slots = nullptr;         // device copy of the slots
   uint32_t* d_uses = nullptr;         // [slots] times the translation used the entry
   uint32_t* d_last = nullptr;         // [slots] clock of the last use or (re-)insertion
+  uint32_t* d_log = nullptr;          // [1 + 2 * kCacheLogCap] count, then (slot, clock) of every use since the last read
+  uint32_t* d_patch = nullptr;        // device side of a packed patch
+  uint32_t* h_stage = nullptr;        // pinned host staging: log read-back, patch upload
+  bool log_pending = false;           // the device log holds entries that have been replayed but not cleared yet
 };

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "ngram_table.h"
 #include "otverify.h"
 
 namespace otv {
@@ -35,19 +36,12 @@ struct CacheTable {
   uint32_t* uses;      // [slots] incremented for every use of the entry by the translation scan
   uint32_t* last_used; // [slots] set to `clock` on use
   uint32_t clock;      // logical time of this step
+  uint32_t* log;       // [1 + 2 * kCacheLogCap] number of uses logged, then (slot, clock) pairs; a use beyond the
+                       // capacity is only counted
 };
-
-__host__ __device__ inline uint32_t hash_ngram(const int32_t* ids, int len) {
-  uint32_t h = 0x9E3779B9u ^ (uint32_t)len;
-  for (int i = 0; i < len; ++i) {
-    h ^= (uint32_t)ids[i] + 0x7F4A7C15u + (h << 6) + (h >> 2);
-    h *= 0x85EBCA6Bu;
-    h ^= h >> 13;
-  }
-  h *= 0xC2B2AE35u;
-  h ^= h >> 16;
-  return h;
-}
+constexpr int kCacheLogCap = 4096;    // uses the device can log between two maintenance calls of a cache
+constexpr int kCacheLogFirst = 64;    // log entries fetched together with the count
+constexpr int kCachePatchCap = 1024;  // slots that travel as a packed patch; more than that uploads the arrays whole
 
 // ------------------------------------------------------------------------------------------------ per-step view
 // What the final-token kernels need to know about sequence b; written by the translate-and-accept kernel.

@@ -95,12 +95,24 @@ def test_online_cache_matches_oracle(policy):
         assert got == ref.snapshot()
         if policy != "none":
             assert len(ref) == capacity                    # the cache ran full and evicted
-        # ---- an export re-inserted into a fresh cache gives the same mapping (save / load round trip)
+        # ---- save / load: an export imported into a fresh cache carries the statistics along, so that both caches go
+        # on evicting the same entries; re-inserting it instead keeps the mapping only
         again = ot.ot_ngram_cache_create(v.ctx, capacity, code)
-        ot.ot_ngram_cache_insert(again, ex["key_off"], ex["key_ids"], ex["target_ids"])
-        got2, _ = _export_as_dict(ot, again)
-        assert {k: t for k, (t, _, _) in got2.items()} == ref.as_dict()
+        ot.ot_ngram_cache_import(again, ex["key_off"], ex["key_ids"], ex["target_ids"], ex["uses"], ex["last_used"])
+        got2, ex2 = _export_as_dict(ot, again)
+        assert got2 == ref.snapshot()
+        assert np.array_equal(ex2["key_ids"], ex["key_ids"]) and np.array_equal(ex2["key_off"], ex["key_off"])   # same insertion order
+        if policy != "none":
+            more = [((90 + i, 91 + i, 92), int(free_targets[i])) for i in range(12)]
+            assert ot.ot_ngram_cache_insert(again, *_csr(more)) == ot.ot_ngram_cache_insert(cache, *_csr(more)) == ref.insert(more)
+            a_state, b_state = _export_as_dict(ot, again)[0], _export_as_dict(ot, cache)[0]
+            assert {k: v[:2] for k, v in a_state.items()} == {k: v[:2] for k, v in b_state.items()} == \
+                   {k: v[:2] for k, v in ref.snapshot().items()}       # same survivors (the two clocks may differ)
         ot.ot_ngram_cache_destroy(again)
+        plain = ot.ot_ngram_cache_create(v.ctx, max(capacity, len(ref)), code)
+        ot.ot_ngram_cache_insert(plain, ex["key_off"], ex["key_ids"], ex["target_ids"])
+        assert {k: t for k, (t, _, _) in _export_as_dict(ot, plain)[0].items()} == {k: t for k, (t, _, _) in got.items()}
+        ot.ot_ngram_cache_destroy(plain)
         # ---- error paths
         if policy == "none":
             full = ot.ot_ngram_cache_create(v.ctx, 2, ot.OT_EVICT_NONE)
@@ -144,4 +156,74 @@ def test_bulk_build_equals_online_inserts():
             assert np.array_equal(a[name], b[name]), name
         assert a["hits_proposed"].sum() > 0
     finally:
+        v.close()
+
+
+@pytest.mark.parametrize("policy", ["lru", "lfu"])
+def test_full_cache_of_100k_entries_evicts_one_entry_per_step(policy):
+    """Steady state of a full cache: every step is followed by an insert that evicts.  The library keeps the eviction
+    order on the host and moves only the touched slots, so a call costs microseconds whatever the cache holds; the
+    state is compared with the oracle's after every tenth step and at the end."""
+    import time
+    from oracle import verify as ov
+    from oracle.ngram_cache import NgramCache
+    from paper_2507_02659_amd import binding as ot
+    from paper_2507_02659_amd.runner import Verifier
+    import parity
+
+    rng = np.random.default_rng(5 if policy == "lru" else 6)
+    capacity = 100_000
+    spec = CaseSpec(name=f"cache_big_{policy}", dtype="f32", d=16, V_t=4000, V_d=3000, k=[8] * 8, temperature=[1.0] * 8,
+                    n_direct=2500, data_seed=31, philox_seed=32, logits_only=True, max_ngram_len=4, align=0.5)
+    case = make_case(spec)
+    free_targets = np.setdiff1d(np.arange(case.V_t), case.direct_map[case.direct_map >= 0])
+    keys = set()
+    while len(keys) < capacity + 64:
+        L = int(rng.integers(2, 5))
+        keys.add(tuple(int(x) for x in rng.integers(0, case.V_d, size=L)))
+    keys = sorted(keys)
+    rng.shuffle(keys)
+    pairs = [(k, int(rng.choice(free_targets))) for k in keys]
+    ref = NgramCache(capacity, policy)
+    code = {"lru": ot.OT_EVICT_LRU, "lfu": ot.OT_EVICT_LFU}[policy]
+    v = Verifier.for_case(case)
+    cache = ot.ot_ngram_cache_create(v.ctx, capacity, code)
+    report = parity.Report()
+    try:
+        ot.ot_ngram_cache_insert(cache, *_csr(pairs[:capacity]))       # fills the cache in one call
+        ref.insert(pairs[:capacity])
+        assert ot.ot_ngram_cache_size(cache)[0] == capacity
+        wall = []
+        for step in range(40):
+            known = pairs[int(rng.integers(0, capacity - 2000)) + 1000][0] if step else pairs[capacity // 2][0]
+            live = [k for k in (known, pairs[capacity - 1 - step][0]) if k in ref.entries]
+            ids = rng.integers(0, case.V_d, size=case.K).astype(np.int32)
+            for b, key in enumerate(live):
+                ids[8 * b:8 * b + len(key)] = key
+            case.draft_ids = ids
+            inp = v.upload(case)
+            sin = ot.make_step_in(B=inp["B"], step=step, row_off=inp["row_off"], row_off_host=inp["row_off_host"], hidden=None,
+                                  draft_logits=inp["draft_logits"], draft_ids=inp["draft_ids"], temperature=inp["temperature"],
+                                  draft_temperature=None, seq_id=inp["seq_id"], seed=inp["seed"])
+            ot.ot_verify_step_from_logits(v.ctx, cache, sin, inp["target_logits"], ot.make_step_out(inp["out"]))
+            gpu = v.results(inp)
+            o = ov.verify_step(row_off=case.row_off, draft_ids=ids, draft_logits=case.draft_logits, direct_map=case.direct_map,
+                               V_t=case.V_t, cache=ref.as_dict(), max_ngram_len=4, temperature=case.temperature, seed=case.seed,
+                               seq_id=case.seq_id, step=step, dtype="f32", target_logits=case.target_logits)
+            ref.record_step(o["used_keys"])
+            report.merge(parity.compare(case, gpu, o, logits_from_gpu=False))
+            new = [pairs[capacity + step]]                            # one unseen pair: one eviction
+            t0 = time.perf_counter()
+            got_evicted = ot.ot_ngram_cache_insert(cache, *_csr(new))
+            wall.append(time.perf_counter() - t0)
+            assert got_evicted == ref.insert(new) == 1
+            if step % 10 == 9:
+                assert _export_as_dict(ot, cache)[0] == ref.snapshot(), step
+        print(f"  insert with one eviction at {capacity} entries: median {1e6 * np.median(wall):.1f} us, "
+              f"max {1e6 * max(wall):.1f} us; " + report.summary(), flush=True)
+        assert not report.failures, "\n".join(report.failures[:10])
+        assert _export_as_dict(ot, cache)[0] == ref.snapshot()
+        assert np.median(wall) < 1e-3          # the whole-table round trip this replaces took several milliseconds
+    finally:
+        ot.ot_ngram_cache_destroy(cache)
         v.close()

@@ -19,6 +19,13 @@ def _say(msg):
     print(msg, flush=True)
 
 
+def _band_budget(B):
+    """Sequences that may sit in a tolerance band.  The bands are 1e-5 (ratio) and 1e-6 of the mass per cell edge (CDF)
+    wide, and a GPU decision differs from the oracle's only when rounding of about 1e-7 (fp32-accumulated logits) or
+    1e-12 (given logits) carries it across: well under 1e-2 per sequence."""
+    return max(1, int(np.ceil(1e-2 * B)))
+
+
 def _run_and_compare(case, *, expect_exact_fraction=0.0, max_divergent=None):
     ov, ot, Verifier, parity = _imports()
     _say(f"case {case.name}: B={case.B} M={case.M} K={case.K} d={case.d} V_t={case.V_t} V_d={case.V_d} {case.dtype}")
@@ -32,7 +39,7 @@ def _run_and_compare(case, *, expect_exact_fraction=0.0, max_divergent=None):
     _say("  " + rep.summary())
     assert not rep.failures, "\n".join(rep.failures[:10])
     if max_divergent is None:
-        max_divergent = max(1, case.B // 8)
+        max_divergent = _band_budget(case.B)
     assert rep.divergent <= max_divergent, rep.summary()
     assert rep.exact >= expect_exact_fraction * rep.sequences
     return gpu, ref, rep
@@ -165,6 +172,46 @@ def test_baseline_configuration(i, greedy):
         assert gpu["hits_proposed"].sum() > 0          # planted cache keys were found by the hash probe
 
 
+@pytest.mark.parametrize("i", [3, 4, 5])
+def test_baseline_configuration_logits_and_row_statistics_elementwise(i):
+    """Full-size LM head (d = 3584 / 4096, V_t = 128256 / 152064, every M-block height the configurations use): every
+    logit against the float64 product, and the row statistics the launch leaves behind against those of the float64
+    logits.  fp32 accumulation of d products of magnitude |h||w| ~ 0.02 puts about sqrt(d) * 2^-24 * 0.02 * 3 ~ 2e-7 on a
+    logit; the bound below leaves a factor of ten."""
+    ov, ot, Verifier, parity = _imports()
+    case = make_case(baseline_spec(i))
+    _say(f"full-size logits, configuration {i}: M={case.M} d={case.d} V_t={case.V_t}")
+    v = Verifier.for_case(case)
+    try:
+        inp = v.upload(case)
+        v.step(inp)
+        ws = v.workspace(case.M, case.K, with_logits=True)
+    finally:
+        v.close()
+    Z = ov.lm_head_logits(case.hidden, case.W, "bf16")
+    atol = 4e-8 * np.sqrt(case.d)
+    np.testing.assert_allclose(ws["logits"], Z, rtol=1e-5, atol=atol)
+    zmax = Z.max(axis=1)
+    np.testing.assert_allclose(ws["row_max"], zmax, rtol=0, atol=2 * atol)
+    arg = ws["row_argmax"].astype(np.int64)
+    assert arg.min() >= 0 and arg.max() < case.V_t
+    assert np.all(Z[np.arange(case.M), arg] >= zmax - 4 * atol)
+    for b in range(case.B):
+        r0, r1 = case.row_off[b], case.row_off[b + 1]
+        T = float(case.temperature[b]) or 1.0
+        want = np.exp((Z[r0:r1] - Z[r0:r1].max(axis=1, keepdims=True)) / T).sum(axis=1)
+        np.testing.assert_allclose(ws["row_sumexp"][r0:r1], want, rtol=1e-4)
+    # the draft rows' statistics (computed next to the LM head) against the widened draft logits
+    Zq = ov.widen(case.draft_logits, "bf16")
+    assert np.array_equal(ws["draft_row_max"].astype(np.float64), Zq.max(axis=1))
+    assert np.array_equal(ws["draft_row_argmax"], Zq.argmax(axis=1))
+    for b in range(case.B):
+        q0, q1 = case.row_off[b] - b, case.row_off[b + 1] - b - 1
+        Td = float(case.temperature[b] if case.draft_temperature is None else case.draft_temperature[b]) or 1.0
+        wantq = np.exp((Zq[q0:q1] - Zq[q0:q1].max(axis=1, keepdims=True)) / Td).sum(axis=1)
+        np.testing.assert_allclose(ws["draft_row_sumexp"][q0:q1], wantq, rtol=2e-6)
+
+
 # --------------------------------------------------------------------------- acceptance chains, bonus tokens, deep rejections
 @pytest.mark.parametrize("dtype,logits_only,seed", [("bf16", False, 1), ("bf16", True, 2), ("f32", False, 3), ("f32", True, 4)])
 def test_agreeable_batches(dtype, logits_only, seed):
@@ -201,7 +248,7 @@ def test_many_steps_monte_carlo_agreement():
         v.close()
     _say("  " + total.summary())
     assert not total.failures, "\n".join(total.failures[:10])
-    assert total.divergent <= 12            # 2400 sequence-steps; bands are ~1e-5 / ~1e-6 wide
+    assert total.divergent <= _band_budget(total.sequences)   # 2400 sequence-steps
 
 
 # --------------------------------------------------------------------------- edge cases
@@ -215,7 +262,7 @@ def test_more_sequences_than_the_lm_head_stages():
     """Above 255 sequences the LM-head epilogue emits no statistics and the separate pass over the logits runs."""
     spec = CaseSpec(name="edge_many_seqs", dtype="bf16", d=64, V_t=1300, V_d=600, k=[1, 0, 2] * 90, temperature=[1.0, 0.0, 0.7] * 90,
                     n_direct=400, n_ngram=100, ngram_len=(2, 3), plant_cover=0.3, align=0.8, data_seed=90, philox_seed=8)
-    _run_and_compare(make_case(spec), max_divergent=4)
+    _run_and_compare(make_case(spec))
 
 
 @pytest.mark.parametrize("M,B", [(16, 2), (17, 2), (33, 3), (96, 6), (97, 6), (144, 9), (145, 9), (288, 12), (289, 12), (300, 255),
@@ -231,7 +278,7 @@ def test_row_count_boundaries_end_to_end(M, B):
                     n_ngram=150, ngram_len=(2, 4), plant_cover=0.4, align=0.8, data_seed=1000 + M + B, philox_seed=9)
     case = make_case(spec)
     assert case.M == M and case.B == B
-    _run_and_compare(case, max_divergent=max(2, B // 8))
+    _run_and_compare(case)
 
 
 @pytest.mark.parametrize("seed", range(24))
@@ -254,7 +301,7 @@ def test_random_shapes_end_to_end(seed):
                     temperature=temps, draft_temperature=draft_t, n_direct=n_direct, n_ngram=n_ngram, ngram_len=(2, lmax),
                     plant_cover=float(rng.choice([0.0, 0.3, 0.7])), align=float(rng.choice([0.0, 0.6, 0.9])), data_seed=9000 + seed,
                     philox_seed=seed, logits_only=bool(rng.integers(0, 2)))
-    _run_and_compare(make_case(spec), max_divergent=max(2, B // 8))
+    _run_and_compare(make_case(spec))
 
 
 def test_draft_temperature_variants():

@@ -128,3 +128,50 @@ def test_used_keys_reported_by_the_verification_oracle():
                        cache=cache, max_ngram_len=3, temperature=[1.0], seed=0, seq_id=[0], step=0, dtype="f32",
                        target_logits=Z)
     assert o["used_keys"] == [(1, 2), (4, 5, 6)] and o["hits_proposed"][0] == 2
+
+
+@pytest.mark.parametrize("policy", ["none", "lru", "lfu"])
+def test_an_insert_call_without_pairs_changes_nothing(policy):
+    """There is no event to date: the clock does not tick, no stamp moves."""
+    c = NgramCache(4, policy)
+    c.insert([((1, 2), 7)])
+    c.record_step([(1, 2)])
+    before = (c.clock, c.snapshot())
+    assert c.insert([]) == 0
+    assert (c.clock, c.snapshot()) == before
+
+
+def test_load_keeps_statistics_and_therefore_the_victims():
+    """Hand example: X was used twice, long ago; Y never, recently.  After a save / load LRU still evicts X first and
+    LFU still evicts Y first; a plain re-insert would have forgotten both facts."""
+    saved = [((1, 2), 10, 2, 5), ((3, 4), 11, 0, 7)]           # (key, target, uses, last_used) in insertion order
+    for policy, victim in (("lru", (1, 2)), ("lfu", (3, 4))):
+        c = NgramCache(2, policy)
+        c.load(saved)
+        assert c.clock == 7 and c.snapshot() == {(1, 2): (10, 2, 5), (3, 4): (11, 0, 7)}
+        assert c.insert([((5, 6), 12)]) == 1
+        assert victim not in c.entries and len(c) == 2
+    with pytest.raises(CacheFull):
+        NgramCache(1, "lru").load(saved)
+
+
+@pytest.mark.parametrize("policy", ["lru", "lfu"])
+def test_export_then_load_continues_like_the_original(policy):
+    rng = random.Random(17)
+    pool = [((a, b), 100 + 7 * a + b) for a in range(6) for b in range(6)]
+    a = NgramCache(9, policy)
+    for _ in range(60):
+        a.insert(rng.sample(pool, rng.randint(1, 3)))
+        a.record_step(rng.choices(list(a.entries), k=rng.randint(0, 3)))
+    b = NgramCache(9, policy)
+    b.load(a.export())
+    b.clock = a.clock                       # the original may have ticked since its latest stamp
+    assert b.snapshot() == a.snapshot()
+    for _ in range(60):
+        items = rng.sample(pool, rng.randint(1, 3))
+        used_from = list(a.entries)
+        assert a.insert(items) == b.insert(items)
+        used = rng.choices(list(a.entries), k=rng.randint(0, 3))
+        a.record_step(used)
+        b.record_step(used)
+        assert a.snapshot() == b.snapshot() and a.export() == b.export()
