@@ -2,8 +2,9 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu]
 
-A "step" is one ot_verify_step over one synthetic batch: draft softmax statistics, translation (direct map +
-n-gram cache), LM-head projection, target softmax statistics, acceptance, residual mass and final-token draw.
+A "step" is one ot_verify_step over one synthetic batch: LM-head projection with the target rows' softmax partials,
+and in the same launch the draft softmax statistics and the translation (direct map + n-gram cache); then acceptance,
+residual masses and the final-token draw.
 The workload is the configuration the headline metric is quoted on: Llama3-8B-shaped target, V_t = 128256,
 B = 16 sequences x k = 8 drafted tokens, bf16 (configuration 4).  Inputs are resident in HBM before the timed
 region.  Prints ONE JSON line.
@@ -29,16 +30,56 @@ def lm_head_bytes(M, d, V_t):
     return 2 * d * V_t + 2 * M * d + 4 * M * V_t
 
 
+def kernel_sources_digest():
+    """Digest of the kernel sources: a counter measurement is valid for exactly the code it was taken on."""
+    import hashlib
+    csrc = os.path.join(ROOT, "paper_2507_02659_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h", ".cpp")):
+            with open(os.path.join(csrc, name), "rb") as f:
+                h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
 def read_traffic_note(path):
-    """HBM bytes per LM-head launch measured offline with rocprofv3 --pmc, if a summary has been committed."""
+    """HBM bytes per LM-head launch measured with rocprofv3 --pmc (two runs: FETCH_SIZE, WRITE_SIZE), from the
+    committed summary -- but only if that summary was taken on the kernel sources of this tree; otherwise None."""
+    value, stamp = None, None
     try:
         with open(path) as f:
             for line in f:
                 if line.startswith("hbm_bytes_per_launch:"):
-                    return float(line.split(":")[1].split()[0])
+                    value = float(line.split(":")[1].split()[0])
+                elif line.startswith("kernel_sources_sha:"):
+                    stamp = line.split(":")[1].strip()
     except OSError:
-        pass
-    return None
+        return None
+    return value if stamp == kernel_sources_digest() else None
+
+
+def measure_cliffs(torch, Verifier):
+    """Step time at the capacity edges the header documents: B = 255 / 256 (fused launch against separate passes) at a
+    mid-size bf16 head, and the one-thread-per-logit fp32 head."""
+    from workloads import CaseSpec, make_case
+    out = {}
+    for name, B, dtype in (("bf16_B255", 255, "bf16"), ("bf16_B256", 256, "bf16"), ("f32_B16", 16, "f32")):
+        spec = CaseSpec(name=name, dtype=dtype, d=1024, V_t=32000, V_d=8000, k=[3] * B, temperature=[1.0] * B, n_direct=6000,
+                        n_ngram=2000, ngram_len=(2, 4), plant_cover=0.3, data_seed=400 + B, philox_seed=1)
+        case = make_case(spec)
+        v = Verifier.for_case(case)
+        inp = v.upload(case)
+        for i in range(5):
+            v.step(inp, step=i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        n = 30
+        for i in range(n):
+            v.step(inp, step=i)
+        torch.cuda.synchronize()
+        out[name] = {"B": B, "rows_M": case.M, "d": 1024, "V_t": 32000, "us_per_step": round(1e6 * (time.perf_counter() - t0) / n, 1)}
+        v.close()
+    return out
 
 
 def main():
@@ -48,6 +89,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=4, help="BASELINE configuration 1..5 (default: the headline one)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--cliffs", action="store_true",
+                    help="also time the capacity edges: 255 against 256 sequences (where the LM-head launch stops hosting "
+                         "the statistics and the draft side) and the fp32 head at a mid size")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (known HBM traffic) so that a rocprofv3 --pmc run of this "
                          "command can scale FETCH_SIZE / WRITE_SIZE of the LM-head kernel against it")
@@ -80,6 +124,16 @@ def main():
     inp = v.upload(case)
     from_logits = case.hidden is None
 
+    # per-kernel durations: HIP events recorded by the library on its own stream between the step's launches (each
+    # event costs the stream about 5 us, so this pass is separate from the timed one)
+    ot.ot_verify_profile(v.ctx, True)
+    n_prof = min(max(args.steps, 20), 1000)
+    for i in range(n_prof):
+        v.step(inp, from_logits=from_logits, step=i)
+    stage_ms, n_read = ot.ot_verify_profile_read(v.ctx)
+    ot.ot_verify_profile(v.ctx, False)
+    stage_us = {k: 1e3 * t / max(n_read, 1) for k, t in stage_ms.items()}
+
     for i in range(args.warmup):
         v.step(inp, from_logits=from_logits, step=i)
     torch.cuda.synchronize()
@@ -91,15 +145,6 @@ def main():
     ms_per_step = 1e3 * elapsed / args.steps
     value = case.K * args.steps / elapsed
 
-    # per-kernel durations: HIP events recorded by the library on its own stream between the step's kernels
-    ot.ot_verify_profile(v.ctx, True)
-    n_prof = min(args.steps, 1000)
-    for i in range(n_prof):
-        v.step(inp, from_logits=from_logits, step=args.warmup + i)
-    stage_ms, n_read = ot.ot_verify_profile_read(v.ctx)
-    ot.ot_verify_profile(v.ctx, False)
-    stage_us = {k: 1e3 * t / max(n_read, 1) for k, t in stage_ms.items()}
-
     # one more step with the benchmark's own step index, kept for the parity note below
     v.step(inp, from_logits=from_logits, step=case.step)
     gpu = v.results(inp)
@@ -109,20 +154,43 @@ def main():
     gemm_bytes = lm_head_bytes(M, d, V_t) if esz == 2 else 4 * d * V_t + 4 * M * d + 4 * M * V_t
     gemm_s = stage_us["lm_head"] * 1e-6
     achieved = gemm_bytes / gemm_s / 1e9 if gemm_s > 0 else 0.0
-    # statistics pass: the draft logits once, plus either the target logits once or, when the LM-head epilogue has
-    # left per-tile softmax partials (bf16, more than 16 rows, at most 255 sequences), those partials
+    # what follows the LM head: with fused statistics one launch (merge of the partials + acceptance + draw), else
+    # statistics, translation + acceptance, draw
     fused = esz == 2 and M > 16 and case.B <= 255 and not from_logits
-    stats_bytes = esz * K * V_d + (12 * M * ((V_t + 255) // 256) if fused else 4 * M * V_t)
+    tail_us = ms_per_step * 1e3 - stage_us["lm_head"]
     extra = {
         "stage_us": {k: round(x, 2) for k, x in stage_us.items()},
+        "stage_us_note": "HIP events on the library's stream; every event adds about 5 us to the stage after it",
+        "after_lm_head_us": round(tail_us, 2),
         "lm_head_tflops": round(2.0 * M * d * V_t / gemm_s / 1e12, 1) if gemm_s > 0 else None,
         "lm_head_frac_mfma_peak": round(2.0 * M * d * V_t / gemm_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4) if gemm_s > 0 else None,
-        "softmax_stats_gbs": round(stats_bytes / (stage_us["softmax_stats"] * 1e-6) / 1e9, 1) if stage_us["softmax_stats"] > 0 else None,
-        "softmax_stats_frac_hbm_peak": round(stats_bytes / (stage_us["softmax_stats"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if stage_us["softmax_stats"] > 0 else None,
         "rows_per_s": round(M * args.steps / elapsed, 1),
-        "step_hbm_bytes": gemm_bytes + stats_bytes + case.B * (4 * V_t + esz * V_d + 4 * V_t),
+        "step_hbm_bytes": gemm_bytes + esz * K * V_d + (16 * M * ((V_t + 255) // 256) if fused else 4 * M * V_t)
+                          + case.B * (4 * V_t + esz * V_d + 4 * V_t),
     }
-    extra["row_statistics"] = "lm_head epilogue" if fused else "separate pass over the logits"
+    extra["row_statistics"] = "lm_head epilogue, draft side in the same launch" if fused else "separate pass over the logits"
+
+    # The softmax pass on its own (the metric's "% HBM BW (softmax)"): the same batch through
+    # ot_verify_step_from_logits with the logits the LM head just produced, so that the statistics kernel reads all
+    # M target rows (fp32) and all K draft rows once.
+    if not from_logits and K > 0:
+        ws = v.workspace(M, K, with_logits=True)
+        inp["target_logits"] = torch.from_numpy(np.ascontiguousarray(ws["logits"])).to("cuda")
+        del ws
+        ot.ot_verify_profile(v.ctx, True)
+        for i in range(50):
+            v.step(inp, from_logits=True, step=i)
+        sm_ms, sm_n = ot.ot_verify_profile_read(v.ctx)
+        ot.ot_verify_profile(v.ctx, False)
+        sm_us = 1e3 * sm_ms["softmax_stats"] / max(sm_n, 1)
+        sm_bytes = 4 * M * V_t + esz * K * V_d
+        extra["softmax_pass"] = {"kernel": "softmax_stats_kernel", "us": round(sm_us, 2), "algorithmic_bytes": sm_bytes,
+                                 "gbs": round(sm_bytes / (sm_us * 1e-6) / 1e9, 1),
+                                 "frac_hbm_peak": round(sm_bytes / (sm_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+                                 "note": "event-timed like stage_us (includes about 5 us of event cost); the rocprofv3 figure is "
+                                         "in profiles/kernel_stats_cfg4_softmax_pass.txt"}
+        inp["target_logits"] = None
+        v.step(inp, from_logits=False, step=case.step)       # back to the batch's own step for what follows
 
     # forward values of the hybrid distillation loss on the same batch (the pass that follows a step when the
     # drafter is trained online): reverse KL on every direct-mapping token, NLL on n-gram tokens
@@ -141,6 +209,8 @@ def main():
         extra["distill_loss"] = {"us_per_call": round(loss_us, 2), "kl_rows": kl_rows, "algorithmic_bytes": loss_bytes,
                                  "gbs": round(loss_bytes / (loss_us * 1e-6) / 1e9, 1), "loss": round(loss["loss"], 6)}
     extra["step_frac_hbm_roofline"] = round(extra["step_hbm_bytes"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    if args.cliffs:
+        extra["cliffs"] = measure_cliffs(torch, Verifier)
 
     result = {
         "metric": "verified draft positions/sec at V_t=128k",

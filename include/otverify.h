@@ -61,6 +61,14 @@ typedef struct ot_ctx ot_ctx;                 /* owns the packed LM head, maps a
 typedef struct ot_ngram_cache ot_ngram_cache; /* owns the device hash table of one n-gram cache               */
 
 /* ---- ot_verify_init ----------------------------------------------------------------------------------- */
+/* The draft rows' softmax statistics and the translation (Eq. 1) need nothing from the LM head.  Where the bf16
+ * LM-head kernel supports it (more than 16 rows, at most 255 sequences) they can run in extra workgroups of the
+ * LM-head launch itself, which then also leaves the target rows' softmax partials, so that one launch follows it
+ * instead of three.  That pays when the weight stream is long enough to hide them. */
+#define OT_DRAFT_SIDE_AUTO        0   /* decide per step from its shape (estimate of both durations)               */
+#define OT_DRAFT_SIDE_IN_LM_HEAD  1   /* inside the LM-head launch whenever the kernel supports the shape          */
+#define OT_DRAFT_SIDE_SEPARATE    2   /* always as launches of their own after the LM head                         */
+
 typedef struct ot_verify_config {
   int32_t d;               /* hidden size; for OT_BF16 a multiple of 8                                        */
   int32_t V_t;             /* target vocabulary size                                                          */
@@ -69,7 +77,7 @@ typedef struct ot_verify_config {
   int32_t max_k;           /* capacity: k_b <= max_k <= OT_MAX_K; rows <= max_batch * (max_k + 1)             */
   int32_t dtype;           /* OT_BF16 or OT_F32: type of W, hidden and draft_logits                           */
   int32_t max_ngram_len;   /* 2..OT_MAX_NGRAM_LEN: longest key any cache used with this context may hold      */
-  int32_t reserved;        /* must be 0                                                                       */
+  int32_t draft_side;      /* OT_DRAFT_SIDE_*: where the part of a step that needs no target logits runs          */
   const void*    W;        /* DEVICE [d, V_t] row-major LM-head weights (z = h . W).  Read during init only:
                               OT_BF16 weights are re-tiled into a private copy, OT_F32 weights are copied.    */
   const int32_t* direct_map; /* HOST [V_d]: target id of each draft id, or -1.  Must be one-to-one on the

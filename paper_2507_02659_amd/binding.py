@@ -25,6 +25,7 @@ OT_N_STAGES = 4
 STAGE_NAMES = ("lm_head", "softmax_stats", "translate_accept", "residual_draw")
 
 OT_EVICT_NONE, OT_EVICT_LRU, OT_EVICT_LFU = 0, 1, 2
+OT_DRAFT_SIDE_AUTO, OT_DRAFT_SIDE_IN_LM_HEAD, OT_DRAFT_SIDE_SEPARATE = 0, 1, 2
 OT_LAMBDA_FIXED, OT_LAMBDA_TARGET_PROB = 0, 1
 OT_NGRAM_TERM_NLL, OT_NGRAM_TERM_APPROX_KL = 0, 1
 
@@ -46,7 +47,7 @@ class OtError(RuntimeError):
 class ot_verify_config(C.Structure):
     _fields_ = [
         ("d", C.c_int32), ("V_t", C.c_int32), ("V_d", C.c_int32), ("max_batch", C.c_int32), ("max_k", C.c_int32),
-        ("dtype", C.c_int32), ("max_ngram_len", C.c_int32), ("reserved", C.c_int32),
+        ("dtype", C.c_int32), ("max_ngram_len", C.c_int32), ("draft_side", C.c_int32),
         ("W", C.c_void_p), ("direct_map", C.c_void_p), ("stream", C.c_void_p),
     ]
 
@@ -182,10 +183,10 @@ def ot_version() -> str:
     return load_library().ot_version().decode()
 
 
-def ot_verify_init(*, d, V_t, V_d, max_batch, max_k, dtype, max_ngram_len, W, direct_map, stream=None, reserved=0):
+def ot_verify_init(*, d, V_t, V_d, max_batch, max_k, dtype, max_ngram_len, W, direct_map, stream=None, draft_side=0):
     """W: device tensor/address [d, V_t]; direct_map: host int32 array [V_d].  Returns the context handle."""
     dm = None if direct_map is None else np.ascontiguousarray(direct_map, dtype=np.int32)
-    cfg = ot_verify_config(d, V_t, V_d, max_batch, max_k, dtype, max_ngram_len, reserved, _ptr(W), _ptr(dm), _ptr(stream))
+    cfg = ot_verify_config(d, V_t, V_d, max_batch, max_k, dtype, max_ngram_len, int(draft_side), _ptr(W), _ptr(dm), _ptr(stream))
     ctx = C.c_void_p()
     _check(load_library().ot_verify_init(C.byref(cfg), C.byref(ctx)))
     return ctx

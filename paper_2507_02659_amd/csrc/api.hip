@@ -71,7 +71,8 @@ int ot_verify_init(const ot_verify_config* cfg, ot_ctx** out) {
     return fail(OT_ERR_SHAPE, "ot_verify_init: need max_batch >= 1 and 0 <= max_k <= %d", OT_MAX_K);
   if (cfg->max_ngram_len < 2 || cfg->max_ngram_len > OT_MAX_NGRAM_LEN)
     return fail(OT_ERR_SHAPE, "ot_verify_init: max_ngram_len must be in 2..%d", OT_MAX_NGRAM_LEN);
-  if (cfg->reserved != 0) return fail(OT_ERR_SHAPE, "ot_verify_init: reserved must be 0");
+  if (cfg->draft_side < OT_DRAFT_SIDE_AUTO || cfg->draft_side > OT_DRAFT_SIDE_SEPARATE)
+    return fail(OT_ERR_SHAPE, "ot_verify_init: draft_side must be one of OT_DRAFT_SIDE_*");
   if ((int64_t)cfg->max_batch * (cfg->max_k + 1) > (1 << 20)) return fail(OT_ERR_SHAPE, "ot_verify_init: more than 2^20 rows");
 
   // direct map: in range and one-to-one on its mapped part
@@ -92,7 +93,7 @@ int ot_verify_init(const ot_verify_config* cfg, ot_ctx** out) {
   ot_ctx* c = new (std::nothrow) ot_ctx();
   if (!c) return fail(OT_ERR_NOMEM, "ot_verify_init: host allocation failed");
   c->d = cfg->d; c->V_t = cfg->V_t; c->V_d = cfg->V_d; c->max_batch = cfg->max_batch; c->max_k = cfg->max_k;
-  c->dtype = cfg->dtype; c->max_ngram_len = cfg->max_ngram_len;
+  c->dtype = cfg->dtype; c->max_ngram_len = cfg->max_ngram_len; c->draft_side = cfg->draft_side;
   c->stream = static_cast<hipStream_t>(cfg->stream);
   c->max_rows = cfg->max_batch * (cfg->max_k + 1);
   c->max_K = cfg->max_batch * cfg->max_k;
@@ -218,7 +219,11 @@ static int step_impl(ot_ctx* ctx, ot_ngram_cache* cache, const ot_step_in* in, c
       // Where its kernel supports it, the LM-head launch leaves per-tile softmax partials of the target rows (no second
       // pass over the logits) and hosts the draft side of the step in extra workgroups: what follows it is then only
       // the merge of those partials with the acceptance test, and the final draw.
-      const int nfine = in->B <= kFusedMaxB ? lmhead_bf16_fused_partials(M, ctx->Vp) : 0;
+      const bool supported = lmhead_bf16_fused_partials(M, ctx->Vp) > 0 && in->B <= kFusedMaxB;
+      const bool host_it = supported && (ctx->draft_side == OT_DRAFT_SIDE_IN_LM_HEAD ||
+                                         (ctx->draft_side == OT_DRAFT_SIDE_AUTO &&
+                                          lmhead_bf16_hosts_draft_side(M, ctx->d, ctx->Vp, in->B, K, ctx->V_d)));
+      const int nfine = host_it ? lmhead_bf16_fused_partials(M, ctx->Vp) : 0;
       if (nfine > 0) {
         a.fused.row_off = in->row_off; a.fused.temperature = in->temperature; a.fused.B = in->B; a.fused.nfine = nfine;
         a.fused.part = ctx->fpart;

@@ -23,6 +23,7 @@
 // Operand roles: the weight fragment is MFMA operand A and the hidden fragment operand B, so a lane ends up with
 // four consecutive vocabulary columns of one row and stores them as one float4.
 #include <algorithm>
+#include <cmath>
 
 #include "translate.h"
 
@@ -455,30 +456,37 @@ __global__ __launch_bounds__(512) void lmhead_bf16_skinny_kernel(const uint16_t*
   }
 }
 
-// fp32 path (small fp32 problems only): one thread per logit, coalesced over the vocabulary.
+// fp32 path (meant for small fp32 problems; no matrix cores): a thread owns one vocabulary column for kF32Rows rows, so
+// a weight is read once per kF32Rows rows, coalesced over the vocabulary, and the hidden values are wave-uniform
+// (scalar loads).  Each logit is one chain of fused multiply-adds in ascending hidden index.
+constexpr int kF32Rows = 8;
 __global__ __launch_bounds__(256) void lmhead_f32_kernel(const float* __restrict__ H, int M, int d,
                                                          const float* __restrict__ W, float* __restrict__ Z, int V_t,
                                                          int64_t ldz) {
   const int n = blockIdx.x * 256 + threadIdx.x;
-  const int m = blockIdx.y;
+  const int m0 = blockIdx.y * kF32Rows;
   if (n >= V_t) return;
-  const float* h = H + (int64_t)m * d;
-  float acc = 0.f;
-  for (int kk = 0; kk < d; ++kk) acc = fmaf(h[kk], W[(int64_t)kk * V_t + n], acc);
-  Z[(int64_t)m * ldz + n] = acc;
+  const int rows = min(kF32Rows, M - m0);
+  float acc[kF32Rows];
+#pragma unroll
+  for (int i = 0; i < kF32Rows; ++i) acc[i] = 0.f;
+  for (int kk = 0; kk < d; ++kk) {
+    const float w = W[(int64_t)kk * V_t + n];
+#pragma unroll
+    for (int i = 0; i < kF32Rows; ++i)
+      if (i < rows) acc[i] = fmaf(H[(int64_t)(m0 + i) * d + kk], w, acc[i]);
+  }
+#pragma unroll
+  for (int i = 0; i < kF32Rows; ++i)
+    if (i < rows) Z[(int64_t)(m0 + i) * ldz + n] = acc[i];
 }
 
-// Workgroups of the launch that run the draft side: as many as the draft logits need to be read well inside the
-// weight stream's time (one workgroup reads on the order of 8 MB in the time an M-block streams the weights), at
-// most one per sequence, and where possible no more than the compute units the last round of multiplying workgroups
-// leaves idle (one workgroup per compute unit), so that they add no round.  A multiple of 8: the XCD mapping holds.
-int draft_side_workgroups(int n_gemm_wgs, const StepArgs& ds) {
-  const int64_t bytes = (int64_t)ds.K * ds.V_d * (ds.dtype == OT_BF16 ? 2 : 4);
-  int want = 8 * (int)std::max<int64_t>(1, (bytes + (8 << 20) - 1) / (8 << 20));
-  const int idle = (256 - n_gemm_wgs % 256) % 256;
-  want = std::min(want, std::max(8, idle / 8 * 8));
-  want = std::min(want, (ds.B + 7) / 8 * 8);
-  return std::min(want, 64);
+// Workgroups of the launch that run the draft side: one per group of kRoleGroup sequences where 64 suffice, at least
+// 8, a multiple of 8 (the XCD mapping of the multiplying workgroups holds).  At the headline shape these fit into the
+// compute units that the last round of multiplying workgroups leaves idle (one workgroup per compute unit).
+int draft_side_workgroups(int B) {
+  const int groups = (B + kRoleGroup - 1) / kRoleGroup;
+  return std::min(64, std::max(8, (groups + 7) / 8 * 8));
 }
 
 template <int MT, int PF, int WPG, int KC, int NW>
@@ -492,7 +500,7 @@ hipError_t launch_wide(const uint16_t* H, int M, int d, const uint16_t* Wp, int 
   int n_role = 0;
   if (draft_side && fs.part) {
     ds = *draft_side;
-    n_role = draft_side_workgroups(col_tiles * m_blocks, ds);
+    n_role = draft_side_workgroups(ds.B);
   }
   dim3 grid(n_role + ceil_div(col_tiles, 8) * 8 * m_blocks), block(WPG * 64);
   const int vec_store = (ldz % 4 == 0) && (reinterpret_cast<uintptr_t>(Z) % 16 == 0);
@@ -514,6 +522,21 @@ hipError_t launch_pack_w_bf16(const uint16_t* W, int d, int V_t, uint16_t* Wp, i
 
 int lmhead_bf16_fused_partials(int M, int Vp) {
   return M > 16 ? Vp / 256 : 0;      // the wide kernels own 256 columns per workgroup; the skinny kernel does not fuse
+}
+
+// Whether the LM-head launch should host the draft side (and leave the softmax partials): only when its few draft-side
+// workgroups finish well inside the time the weights take to stream.  Estimates: a draft-side workgroup reads about
+// 10 GB/s next to the saturating weight stream (measured at the headline shape: 1 MB in 100 us) and spends about 20 us
+// per group of sequences on dependent loads; the product streams 5.5 TB/s or runs 1 PFLOP/s, whichever takes longer.
+bool lmhead_bf16_hosts_draft_side(int M, int d, int Vp, int B, int K, int V_d) {
+  if (lmhead_bf16_fused_partials(M, Vp) == 0 || B < 1 || B > kFusedMaxB) return false;
+  const int n_role = draft_side_workgroups(B);
+  const double groups = std::ceil(std::ceil((double)B / n_role) / kRoleGroup);   // taken one after the other
+  const double per_wg = std::ceil((double)B / n_role);              // sequences a workgroup owns
+  const double bytes_per_group = (double)K / B * std::min<double>(kRoleGroup, per_wg) * V_d * 2.0;
+  const double role_us = groups * (20.0 + bytes_per_group / 10e3);
+  const double gemm_us = std::max(2.0 * d * Vp / 5.5e6, 2.0 * M * d * (double)Vp / 1.0e9);
+  return role_us <= gemm_us;
 }
 
 hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
@@ -561,7 +584,7 @@ hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* W
 hipError_t launch_lmhead_f32(const float* H, int M, int d, const float* W, float* Z, int V_t, int64_t ldz,
                              hipStream_t stream) {
   if (M == 0) return hipSuccess;
-  hipLaunchKernelGGL(lmhead_f32_kernel, dim3(ceil_div(V_t, 256), M), dim3(256), 0, stream, H, M, d, W, Z, V_t, ldz);
+  hipLaunchKernelGGL(lmhead_f32_kernel, dim3(ceil_div(V_t, 256), ceil_div(M, kF32Rows)), dim3(256), 0, stream, H, M, d, W, Z, V_t, ldz);
   return hipGetLastError();
 }
 

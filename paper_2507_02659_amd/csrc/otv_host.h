@@ -13,7 +13,7 @@ int ot_fail_hip(hipError_t e, const char* what);
 int ot_static_scratch_prepare();
 
 struct ot_ctx {
-  int32_t d = 0, V_t = 0, V_d = 0, max_batch = 0, max_k = 0, dtype = 0, max_ngram_len = 0;
+  int32_t d = 0, V_t = 0, V_d = 0, max_batch = 0, max_k = 0, dtype = 0, max_ngram_len = 0, draft_side = 0;
   int32_t max_rows = 0, max_K = 0, Kp = 0, Vp = 0, ncht = 0, nchd = 0, ntiles = 0;
   hipStream_t stream = nullptr;
   int device = 0;

@@ -11,7 +11,7 @@ namespace otv {
 
 // ------------------------------------------------------------------------------------------------ geometry
 constexpr int kStatThreads = 256;
-constexpr int kStatChunk = 4096;     // logits per workgroup of the softmax-statistics kernel
+constexpr int kStatChunk = 8192;     // logits per workgroup of the softmax-statistics kernel (measured: 4096 and 16384 are slower)
 constexpr int kResidTile = 1024;     // vocabulary entries per workgroup of the residual kernel
 constexpr int kGemmColsPerWave = 64; // LM-head columns owned by one wavefront
 constexpr int kGemmKPad = 128;       // packed K extent is a multiple of this
@@ -139,6 +139,9 @@ hipError_t launch_pack_w_bf16(const uint16_t* W, int d, int V_t, uint16_t* Wp, i
 // Partials per row that launch_lmhead_bf16 emits for M rows of a Vp-column (padded) head; 0: that shape runs a
 // kernel without the fused statistics.
 int lmhead_bf16_fused_partials(int M, int Vp);
+// Whether a step of this shape lets the LM-head launch host the draft side and emit the partials (else the step runs
+// the statistics and the translation as launches of their own).
+bool lmhead_bf16_hosts_draft_side(int M, int d, int Vp, int B, int K, int V_d);
 // `fused` may be nullptr or have part == nullptr (no statistics); otherwise fused->nfine must be
 // lmhead_bf16_fused_partials(M, Vp) > 0 and fused->B <= kFusedMaxB.  With fused statistics and `draft_side` not
 // nullptr, extra workgroups of the same launch run the draft side of the step (draft row statistics, translation,

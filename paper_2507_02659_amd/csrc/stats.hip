@@ -14,7 +14,7 @@ namespace otv {
 namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr int kPerThread = kStatChunk / kStatThreads;   // 16 logits per thread
+constexpr int kPerThread = kStatChunk / kStatThreads;   // 32 logits per thread
 
 // Sequence that owns `row`: rows of sequence b start at off[b] - shift*b (shift = 0 target rows, 1 draft rows).
 __device__ inline int find_sequence(const int32_t* off, int B, int row, int shift) {

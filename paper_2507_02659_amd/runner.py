@@ -38,7 +38,7 @@ class Verifier:
     """One library context plus (optionally) one n-gram cache, for batches of a fixed model shape."""
 
     def __init__(self, *, d, V_t, V_d, dtype: str, W, direct_map, max_batch, max_k, max_ngram_len=2,
-                 device="cuda:0", stream: Optional[torch.cuda.Stream] = None):
+                 device="cuda:0", stream: Optional[torch.cuda.Stream] = None, draft_side: int = ot.OT_DRAFT_SIDE_AUTO):
         if not torch.cuda.is_available():
             raise RuntimeError("otverify needs a GPU: there is no CPU path")
         self.device = torch.device(device)
@@ -52,7 +52,7 @@ class Verifier:
         self.ctx = ot.ot_verify_init(d=d, V_t=V_t, V_d=V_d, max_batch=max_batch, max_k=max_k,
                                      dtype=ot.OT_BF16 if dtype == "bf16" else ot.OT_F32, max_ngram_len=max_ngram_len,
                                      W=W_dev, direct_map=direct_map,
-                                     stream=None if stream is None else stream.cuda_stream)
+                                     stream=None if stream is None else stream.cuda_stream, draft_side=draft_side)
         del W_dev                                   # init keeps a private re-tiled copy
         self.cache = None
         self._keep = None

@@ -74,7 +74,7 @@ def test_init_argument_errors_need_no_gpu():
     assert code(max_k=64) == ot.OT_ERR_SHAPE
     assert code(max_ngram_len=1) == ot.OT_ERR_SHAPE
     assert code(max_ngram_len=9) == ot.OT_ERR_SHAPE
-    assert code(reserved=1) == ot.OT_ERR_SHAPE
+    assert code(draft_side=3) == ot.OT_ERR_SHAPE and code(draft_side=-1) == ot.OT_ERR_SHAPE
     dm = np.full(50, -1, np.int32)
     dm[3] = 100
     assert code(direct_map=dm) == ot.OT_ERR_MAP          # out of range

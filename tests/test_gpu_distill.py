@@ -28,7 +28,7 @@ def _compare(case, *, rtol, atol, with_qprime=False, modes=MODES):
     from_logits = case.hidden is None
     _say(f"loss case {case.name}: B={case.B} M={case.M} V_t={case.V_t} V_d={case.V_d} {case.dtype} from_logits={from_logits}")
     ref = ov.verify_case(case)
-    v = Verifier.for_case(case)
+    v = Verifier.for_case(case, draft_side=ot.OT_DRAFT_SIDE_IN_LM_HEAD)     # the row statistics the loss reads come from the LM-head launch where it supports the shape
     try:
         inp = v.upload(case)
         v.step(inp, from_logits=from_logits)

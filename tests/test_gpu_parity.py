@@ -27,21 +27,26 @@ def _band_budget(B):
 
 
 def _run_and_compare(case, *, expect_exact_fraction=0.0, max_divergent=None):
+    """One step through the library against the oracle.  A bf16 batch with hidden states runs twice: with the draft
+    side hosted by the LM-head launch (where that kernel supports the shape) and with every stage as its own launch;
+    the estimate that picks between the two in production would send every small test shape down the second path."""
     ov, ot, Verifier, parity = _imports()
     _say(f"case {case.name}: B={case.B} M={case.M} K={case.K} d={case.d} V_t={case.V_t} V_d={case.V_d} {case.dtype}")
-    v = Verifier.for_case(case)
-    try:
-        gpu = v.run_case(case)
-    finally:
-        v.close()
     ref = ov.verify_case(case)
-    rep = parity.compare(case, gpu, ref, logits_from_gpu=case.hidden is not None)
-    _say("  " + rep.summary())
-    assert not rep.failures, "\n".join(rep.failures[:10])
-    if max_divergent is None:
-        max_divergent = _band_budget(case.B)
-    assert rep.divergent <= max_divergent, rep.summary()
-    assert rep.exact >= expect_exact_fraction * rep.sequences
+    both = case.hidden is not None and case.dtype == "bf16"
+    gpu = rep = None
+    for policy in ((ot.OT_DRAFT_SIDE_SEPARATE, ot.OT_DRAFT_SIDE_IN_LM_HEAD) if both else (ot.OT_DRAFT_SIDE_AUTO,)):
+        v = Verifier.for_case(case, draft_side=policy)
+        try:
+            gpu = v.run_case(case)
+        finally:
+            v.close()
+        rep = parity.compare(case, gpu, ref, logits_from_gpu=case.hidden is not None)
+        _say(f"  draft_side={policy}: " + rep.summary())
+        assert not rep.failures, "\n".join(rep.failures[:10])
+        budget = _band_budget(case.B) if max_divergent is None else max_divergent
+        assert rep.divergent <= budget, rep.summary()
+        assert rep.exact >= expect_exact_fraction * rep.sequences
     return gpu, ref, rep
 
 
@@ -142,7 +147,7 @@ def test_row_statistics_from_lm_head_epilogue(M, d, V_t):
     case = make_case(spec)
     assert case.M == M
     _say(f"fused statistics case M={M} d={d} V_t={V_t}")
-    v = Verifier.for_case(case)
+    v = Verifier.for_case(case, draft_side=ot.OT_DRAFT_SIDE_IN_LM_HEAD)
     try:
         inp = v.upload(case)
         v.step(inp)
@@ -176,12 +181,14 @@ def test_baseline_configuration(i, greedy):
 def test_baseline_configuration_logits_and_row_statistics_elementwise(i):
     """Full-size LM head (d = 3584 / 4096, V_t = 128256 / 152064, every M-block height the configurations use): every
     logit against the float64 product, and the row statistics the launch leaves behind against those of the float64
-    logits.  fp32 accumulation of d products of magnitude |h||w| ~ 0.02 puts about sqrt(d) * 2^-24 * 0.02 * 3 ~ 2e-7 on a
-    logit; the bound below leaves a factor of ten."""
+    logits.  The kernel adds d/32 MFMA partial products in fp32: a running sum of magnitude up to ~2 is rounded to
+    2^-24 relative at each of the d/32 additions, a random walk of about sqrt(d/32) * 1.2e-7 = 1.3e-6 at d = 4096
+    (standard deviation); over the 18 to 65 million logits of these cases the largest deviation reaches five to six
+    of those, so the absolute bound is 1.5e-7 * sqrt(d) (seven standard deviations), next to 1e-5 relative."""
     ov, ot, Verifier, parity = _imports()
     case = make_case(baseline_spec(i))
     _say(f"full-size logits, configuration {i}: M={case.M} d={case.d} V_t={case.V_t}")
-    v = Verifier.for_case(case)
+    v = Verifier.for_case(case, draft_side=ot.OT_DRAFT_SIDE_IN_LM_HEAD)
     try:
         inp = v.upload(case)
         v.step(inp)
@@ -189,7 +196,7 @@ def test_baseline_configuration_logits_and_row_statistics_elementwise(i):
     finally:
         v.close()
     Z = ov.lm_head_logits(case.hidden, case.W, "bf16")
-    atol = 4e-8 * np.sqrt(case.d)
+    atol = 1.5e-7 * np.sqrt(case.d)
     np.testing.assert_allclose(ws["logits"], Z, rtol=1e-5, atol=atol)
     zmax = Z.max(axis=1)
     np.testing.assert_allclose(ws["row_max"], zmax, rtol=0, atol=2 * atol)
@@ -329,7 +336,7 @@ def test_no_cache_and_empty_cache_agree():
     spec = CaseSpec(name="edge_nocache", dtype="bf16", d=64, V_t=2000, V_d=2000, k=[5] * 6, temperature=[1.0] * 6,
                     identity_map=True, permute_frac=0.1, align=0.6, data_seed=91, philox_seed=9)
     case = make_case(spec)
-    v = Verifier.for_case(case)
+    v = Verifier.for_case(case, draft_side=ot.OT_DRAFT_SIDE_IN_LM_HEAD)
     try:
         a = v.run_case(case)                      # empty cache object
         b = v.run_case(case, use_cache=False)     # NULL cache
@@ -380,7 +387,7 @@ def test_eq2_override_on_shared_target_id():
 def test_determinism_bitwise():
     ov, ot, Verifier, parity = _imports()
     case = make_case(baseline_spec(4, scale={"d": 512, "V_t": 20000, "V_d": 8000, "n_direct": 6000, "n_ngram": 3000}))
-    v = Verifier.for_case(case)
+    v = Verifier.for_case(case, draft_side=ot.OT_DRAFT_SIDE_IN_LM_HEAD)
     try:
         first = v.run_case(case)
         for _ in range(3):
