@@ -46,6 +46,11 @@ extern "C" {
 #define OT_ERR_NOMEM         -8   /* host or device allocation failed                                        */
 
 /* ---- storage types of hidden states, LM-head weights and draft logits --------------------------------- */
+/* OT_BF16 is the production type: the LM head runs on the matrix cores, bound by the weight stream.
+ * OT_F32 exists for small problems that want fp32 arithmetic end to end (checks against an fp32 model, toy
+ * vocabularies): its LM head is a vector-ALU kernel that re-reads W once per 8 rows and never hosts the draft side,
+ * so a step costs several times the bf16 one at the same shape (measured: about 6x at d = 4096, V_t = 128256,
+ * 144 rows).  Nothing is refused for size; it is simply slow there.                                          */
 #define OT_BF16 0
 #define OT_F32  1
 
@@ -65,6 +70,12 @@ typedef struct ot_ngram_cache ot_ngram_cache; /* owns the device hash table of o
  * LM-head kernel supports it (more than 16 rows, at most 255 sequences) they can run in extra workgroups of the
  * LM-head launch itself, which then also leaves the target rows' softmax partials, so that one launch follows it
  * instead of three.  That pays when the weight stream is long enough to hide them. */
+/* Capacity edges (all shapes inside max_batch / max_k are served; what changes is the launch structure):
+ *   - more than 255 sequences in a step, 16 rows or fewer, OT_F32, or a step entered through
+ *     ot_verify_step_from_logits: the draft side always runs as launches of its own after the LM head (two more
+ *     launches, about 10 us at 16 sequences, about 25 us at 256 with a 32000-id draft vocabulary);
+ *   - OT_DRAFT_SIDE_AUTO also chooses that structure when hosting would lengthen the LM-head launch, e.g. many
+ *     sequences over a short weight stream.                                                                   */
 #define OT_DRAFT_SIDE_AUTO        0   /* decide per step from its shape (estimate of both durations)               */
 #define OT_DRAFT_SIDE_IN_LM_HEAD  1   /* inside the LM-head launch whenever the kernel supports the shape          */
 #define OT_DRAFT_SIDE_SEPARATE    2   /* always as launches of their own after the LM head                         */

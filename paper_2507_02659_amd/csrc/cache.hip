@@ -62,9 +62,10 @@ int pull_use_log(ot_ngram_cache* c) {
     e = hipMemcpy(h + first, c->d_log + first, 2 * (size_t)(count - kCacheLogFirst) * sizeof(uint32_t), hipMemcpyDeviceToHost);
     if (e != hipSuccess) return ot_fail_hip(e, "n-gram cache: reading the use log");
   }
-  for (uint32_t i = 0; i < count; ++i) {
+  for (uint32_t i = c->log_replayed; i < count; ++i) {
     if (!c->tab.record_use(h[1 + 2 * i], h[2 + 2 * i])) return ot_fail(OT_ERR_HIP, "n-gram cache: the use log names an empty slot");
   }
+  c->log_replayed = count;
   return OT_OK;
 }
 
@@ -99,6 +100,7 @@ int push_changes(ot_ngram_cache* c) {
   e = hipGetLastError();
   if (e != hipSuccess) return ot_fail_hip(e, "n-gram cache: patch launch");
   c->log_pending = false;
+  c->log_replayed = 0;
   return OT_OK;
 }
 

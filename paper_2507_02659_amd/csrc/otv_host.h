@@ -52,4 +52,6 @@ struct ot_ngram_cache {
   uint32_t* d_patch = nullptr;        // device side of a packed patch
   uint32_t* h_stage = nullptr;        // pinned host staging: log read-back, patch upload
   bool log_pending = false;           // the device log holds entries that have been replayed but not cleared yet
+  uint32_t log_replayed = 0;          // how many of them: a call that fails before the log is cleared leaves them
+                                      // there, and the next call must not count those uses a second time
 };

@@ -86,6 +86,14 @@ def test_online_cache_matches_oracle(policy):
             report.merge(parity.compare(case, gpu, o, logits_from_gpu=False))
             assert o["hits_proposed"].sum() >= 1
             if step % 5 == 4:
+                if step % 10 == 9:
+                    # a maintenance call that fails after it has read the device's use log (no room for the entries)
+                    # leaves the log in place; the uses in it must not be counted again by the next call
+                    tiny = np.zeros(4, np.int32)
+                    with pytest.raises(ot.OtError) as e:
+                        ot._check(ot.load_library().ot_ngram_cache_export(cache, 0, 0, ot._ptr(tiny), ot._ptr(tiny), ot._ptr(tiny),
+                                                                        None, None))
+                    assert e.value.code == ot.OT_ERR_SHAPE
                 got, _ = _export_as_dict(ot, cache)
                 assert got == ref.snapshot(), step
         print("  " + report.summary(), flush=True)
