@@ -95,7 +95,7 @@ __device__ inline void lds_barrier() {
 
 constexpr int gcd_c(int a, int b) { return b == 0 ? a : gcd_c(b, a % b); }
 
-template <int MT, int PF, int WPG, int KC, int NW>
+template <int MT, int PF, int WPG, int KC, int NW, bool W_ONCE>
 __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16_t* __restrict__ H, int M, int d,
                                                                     const uint4* __restrict__ Wp, int nks,
                                                                     int n_wtiles, float* __restrict__ Z, int V_t,
@@ -136,8 +136,8 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
   // of the draft rows, translation into the target vocabulary, parked proposals), which needs none of the logits, while
   // the other workgroups stream the weights.  n_role is a multiple of 8, so the mapping below keeps its XCD.
   if ((int)blockIdx.x < n_role) {
-    static_assert(sizeof(RoleLds) <= sizeof(sPatch) && WPG == kRoleWaves, "the draft side's scratch fits into the epilogue patch");
-    draft_side_workgroup<uint16_t>(ds, blockIdx.x, n_role, tid, reinterpret_cast<RoleLds*>(&sPatch[0][0]));
+    static_assert(sizeof(RoleLds) <= sizeof(sPatch), "the draft side's scratch fits into the epilogue patch");
+    draft_side_workgroup<uint16_t, WPG>(ds, blockIdx.x, n_role, tid, reinterpret_cast<RoleLds*>(&sPatch[0][0]));
     return;
   }
   const int wg = (int)blockIdx.x - n_role;
@@ -189,11 +189,15 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
     return (s == 0 ? sW0 : s == 1 ? sW1 : s == 2 ? sW2 : s == 3 ? sW3 : s == 4 ? sW4 : sW5) + wave * (NW * 64);
   };
   // fetch the fragments of step kf into this wavefront's part of ring array s
+  // With a single M-block every weight is read exactly once by the whole launch: those loads are marked nontemporal
+  // (cache-policy bit 1 of the load), which a plain streaming read of the same bytes was measured to gain 12 % from
+  // (7.05 against 6.3 TB/s).  With several M-blocks the later ones find the weights in L2 and the mark would not help.
+  constexpr int kWeightPolicy = W_ONCE ? 2 : 0;
   auto fetch_w = [&](int kf, int s) {
 #pragma unroll
     for (int nw = 0; nw < NW; ++nw)
       __builtin_amdgcn_global_load_lds((glb_ptr_t)(wp + ((int64_t)kf * 4 + nw) * 64), (lds_ptr_t)(ring(s) + nw * 64), 16,
-                                       0, 0);
+                                       0, kWeightPolicy);
   };
 
   request(0, sA);
@@ -388,6 +392,7 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
 // over its 8 wavefronts, so that even a 32000-column head yields thousands of wavefronts streaming W; the hidden
 // fragments are tiny and read straight from global memory (L2 resident).  The 8 partial tiles are summed through
 // LDS in a fixed order.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 template <int PF>
 __global__ __launch_bounds__(512) void lmhead_bf16_skinny_kernel(const uint16_t* __restrict__ H, int M, int d,
                                                                  const uint4* __restrict__ Wp, int nks,
@@ -408,7 +413,10 @@ __global__ __launch_bounds__(512) void lmhead_bf16_skinny_kernel(const uint16_t*
   uint4 bq[PF][4], hq[PF];
   auto fetch = [&](int slot, int ks) {
 #pragma unroll
-    for (int nw = 0; nw < 4; ++nw) bq[slot][nw] = wp[((int64_t)ks * 4 + nw) * 64];
+    for (int nw = 0; nw < 4; ++nw) {               // read once by the whole launch: nontemporal (see the wide kernel)
+      const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wp + ((int64_t)ks * 4 + nw) * 64));
+      bq[slot][nw] = make_uint4(v.x, v.y, v.z, v.w);
+    }
     hq[slot] = make_uint4(0, 0, 0, 0);
     if (h_ok && ks * 32 + h_col < d) hq[slot] = *reinterpret_cast<const uint4*>(hp + ks * 32);
   };
@@ -489,7 +497,7 @@ int draft_side_workgroups(int B) {
   return std::min(64, std::max(8, (groups + 7) / 8 * 8));
 }
 
-template <int MT, int PF, int WPG, int KC, int NW>
+template <int MT, int PF, int WPG, int KC, int NW, bool W_ONCE = false>
 hipError_t launch_wide(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
                        int64_t ldz, const uint16_t* zeros, const FusedStats& fs, const StepArgs* draft_side,
                        hipStream_t stream) {
@@ -504,7 +512,8 @@ hipError_t launch_wide(const uint16_t* H, int M, int d, const uint16_t* Wp, int 
   }
   dim3 grid(n_role + ceil_div(col_tiles, 8) * 8 * m_blocks), block(WPG * 64);
   const int vec_store = (ldz % 4 == 0) && (reinterpret_cast<uintptr_t>(Z) % 16 == 0);
-  hipLaunchKernelGGL((lmhead_bf16_wide_kernel<MT, PF, WPG, KC, NW>), grid, block, 0, stream, H, M, d,
+  if (W_ONCE && m_blocks != 1) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((lmhead_bf16_wide_kernel<MT, PF, WPG, KC, NW, W_ONCE>), grid, block, 0, stream, H, M, d,
                      reinterpret_cast<const uint4*>(Wp), nks, n_wtiles, Z, V_t, ldz, vec_store, zeros, m_blocks, fs, n_role,
                      ds);
   return hipGetLastError();
@@ -556,10 +565,10 @@ hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* W
                        reinterpret_cast<const uint4*>(Wp), nks, Z, V_t, ldz);
     return hipGetLastError();
   }
-  if (tiles <= 2) return launch_wide<2, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
-  if (tiles <= 4) return launch_wide<4, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
-  if (tiles <= 6) return launch_wide<6, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
-  if (tiles <= 9) return launch_wide<9, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
+  if (tiles <= 2) return launch_wide<2, 4, 8, 128, 2, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
+  if (tiles <= 4) return launch_wide<4, 4, 8, 128, 2, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
+  if (tiles <= 6) return launch_wide<6, 4, 8, 128, 2, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
+  if (tiles <= 9) return launch_wide<9, 4, 8, 128, 2, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
   // More than 144 rows run as several M-blocks per column tile; their weight streams meet in one L2.  This regime is
   // bound by the L2 -> LDS traffic and by LDS reads, and the time of an M-block was measured to grow almost in
   // proportion to its height (about 1.3 row tiles of fixed cost per block: 144, 256, 288 rows take 150, 251, 284 us at

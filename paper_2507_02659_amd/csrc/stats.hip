@@ -30,7 +30,8 @@ template <typename T> struct Loader;
 template <> struct Loader<float> {
   static constexpr int kVec = 4;
   __device__ static void load(const float* p, float* v) {
-    float4 x = *reinterpret_cast<const float4*>(p);
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const f32x4 x = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));   // a pass over rows far larger than L2
     v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
   }
   __device__ static float one(const float* p) { return *p; }
@@ -38,7 +39,8 @@ template <> struct Loader<float> {
 template <> struct Loader<uint16_t> {
   static constexpr int kVec = 8;
   __device__ static void load(const uint16_t* p, float* v) {
-    uint4 x = *reinterpret_cast<const uint4*>(p);
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
     uint32_t w[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {

@@ -328,21 +328,21 @@ __device__ inline void fetch_proposal(const RowProposal* rec, LaneProposal* P) {
   P->lq = r.lq; P->lq_first = r.lq_first; P->Sq = r.Sq;
 }
 
-// The draft side of a share of the batch by one workgroup of 8 wavefronts (all threads call it; it contains workgroup
+// The draft side of a share of the batch by one workgroup of kWaves >= kRoleGroup wavefronts (all threads call it; it contains workgroup
 // barriers).  Workgroup wg of n_wg owns the sequences b = wg, wg + n_wg, ..; it takes them kRoleGroup at a time so that
 // their dependent loads (row offsets -> drafted ids -> table slots) are in flight side by side: the drafted positions
 // and the probe windows of the whole group are spread over all threads, the group's draft rows over the wavefronts,
 // and wavefront s then walks sequence s of the group and parks one RowProposal per row of it.
 constexpr int kRoleGroup = 4;
-constexpr int kRoleWaves = 8;
 struct RoleLds {
   DraftLds seq[kRoleGroup];
   int32_t b[kRoleGroup], r0[kRoleGroup], k[kRoleGroup];   // k < 0: the slot is unused
   float Td[kRoleGroup];
 };
 
-template <typename TD>
+template <typename TD, int kWaves>
 __device__ inline void draft_side_workgroup(const StepArgs& a, int wg, int n_wg, int tid, RoleLds* R) {
+  static_assert(kWaves >= kRoleGroup, "one walking wavefront per sequence of a group");
   const int wave = tid >> 6, lane = tid & 63;
   for (int b0 = wg; b0 < a.B; b0 += kRoleGroup * n_wg) {
     __syncthreads();                             // the previous group's walks have finished with R
@@ -369,12 +369,12 @@ __device__ inline void draft_side_workgroup(const StepArgs& a, int wg, int n_wg,
     for (int s = 0; s < kRoleGroup; ++s) {
       const int k = R->k[s];
       if (k > 0) {
-        const int g = (tid + kRoleWaves * 64 - (s * 128) % (kRoleWaves * 64)) % (kRoleWaves * 64);
-        fetch_ids_and_probe(a, R->r0[s] - R->b[s], k, g, kRoleWaves * 64, &R->seq[s]);
+        const int g = (tid + kWaves * 64 - (s * 128) % (kWaves * 64)) % (kWaves * 64);
+        fetch_ids_and_probe(a, R->r0[s] - R->b[s], k, g, kWaves * 64, &R->seq[s]);
       }
     }
     // draft rows of the group, one wavefront per row
-    for (int f = wave; f < first[kRoleGroup]; f += kRoleWaves) {
+    for (int f = wave; f < first[kRoleGroup]; f += kWaves) {
       int s = 0;
 #pragma unroll
       for (int t = 1; t < kRoleGroup; ++t) s += (f >= first[t]) ? 1 : 0;
