@@ -185,7 +185,7 @@ static int step_impl(ot_ctx* ctx, ot_ngram_cache* cache, const ot_step_in* in, c
   if (cache && cache->tab.size() > 0) {
     a.cache.slots = cache->d_slots; a.cache.mask = cache->tab.mask(); a.cache.stride = cache->tab.stride();
     a.cache.max_len = cache->tab.max_len(); a.cache.uses = cache->d_uses; a.cache.last_used = cache->d_last;
-    a.cache.clock = cache->tab.clock(); a.cache.log = cache->d_log;
+    a.cache.clock = cache->tab.clock(); a.cache.log_count = cache->d_log_count; a.cache.log = cache->d_log;
   }
   a.Z = from_logits ? ext_logits : ctx->Z;
   a.ldz = ctx->V_t;

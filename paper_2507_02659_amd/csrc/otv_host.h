@@ -48,9 +48,11 @@ struct ot_ngram_cache {
   int32_t* d_slots = nullptr;         // device copy of the slots
   uint32_t* d_uses = nullptr;         // [slots] times the translation used the entry
   uint32_t* d_last = nullptr;         // [slots] clock of the last use or (re-)insertion
-  uint32_t* d_log = nullptr;          // [1 + 2 * kCacheLogCap] count, then (slot, clock) of every use since the last read
-  uint32_t* d_patch = nullptr;        // device side of a packed patch
-  uint32_t* h_stage = nullptr;        // pinned host staging: log read-back, patch upload
+  uint32_t* d_log_count = nullptr;    // device word: number of uses the device logged since the log was cleared
+  uint2* h_log = nullptr;             // [kCacheLogCap] pinned host memory: (slot + 1, clock) of every such use, written by the device
+  uint2* d_log = nullptr;             // the same memory as the device addresses it
+  uint32_t* h_stage = nullptr;        // pinned host memory that holds a packed patch; the patch kernel reads it in place
+  uint32_t* d_stage = nullptr;        // the same memory as the device addresses it
   bool log_pending = false;           // the device log holds entries that have been replayed but not cleared yet
   uint32_t log_replayed = 0;          // how many of them: a call that fails before the log is cleared leaves them
                                       // there, and the next call must not count those uses a second time

@@ -36,11 +36,11 @@ struct CacheTable {
   uint32_t* uses;      // [slots] incremented for every use of the entry by the translation scan
   uint32_t* last_used; // [slots] set to `clock` on use
   uint32_t clock;      // logical time of this step
-  uint32_t* log;       // [1 + 2 * kCacheLogCap] number of uses logged, then (slot, clock) pairs; a use beyond the
-                       // capacity is only counted
+  uint32_t* log_count; // device word: uses logged since the log was last cleared (a use beyond the capacity is only counted)
+  uint2* log;          // [kCacheLogCap] (slot + 1, clock) of those uses, in pinned HOST memory that the device writes
+                       // directly: the maintenance calls read it without a copy; 0 marks an entry not written yet
 };
 constexpr int kCacheLogCap = 4096;    // uses the device can log between two maintenance calls of a cache
-constexpr int kCacheLogFirst = 64;    // log entries fetched together with the count
 constexpr int kCachePatchCap = 1024;  // slots that travel as a packed patch; more than that uploads the arrays whole
 
 // ------------------------------------------------------------------------------------------------ per-step view

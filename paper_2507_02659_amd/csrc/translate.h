@@ -281,8 +281,8 @@ __device__ inline void translate_walk(const StepArgs& a, int b, int r0, int k, i
     // use statistics of the entry (Appendix, cache eviction): one more use, last used now
     atomicAdd(&a.cache.uses[slot_j], 1u);
     a.cache.last_used[slot_j] = a.cache.clock;
-    const uint32_t at = atomicAdd(&a.cache.log[0], 1u);          // and the host hears of it through the log
-    if (at < (uint32_t)kCacheLogCap) { a.cache.log[1 + 2 * at] = (uint32_t)slot_j; a.cache.log[2 + 2 * at] = a.cache.clock; }
+    const uint32_t at = atomicAdd(a.cache.log_count, 1u);        // and the host hears of it through the log
+    if (at < (uint32_t)kCacheLogCap) a.cache.log[at] = make_uint2((uint32_t)slot_j + 1u, a.cache.clock);
   }
   // the draft row a final draw at this position would read
   const int s_fin = lane < m ? start_j : ((lane == m && s_end < k) ? s_end : -1);
