@@ -67,6 +67,7 @@ __global__ __launch_bounds__(256) void pack_w_kernel(const uint16_t* __restrict_
 // MFMAs, and one barrier per slice hands the buffers over.  LDS rows are unpadded; the 16-byte chunks of a row are
 // XOR-swizzled with the row index (applied on the global side of the copy, since a direct load writes consecutive
 // lanes to consecutive LDS addresses) so that the 16 rows a fragment read touches fall into 16 distinct bank groups.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 
@@ -106,7 +107,7 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
   constexpr int kCPR = KC / 8;                     // 16-byte chunks per slice row
   constexpr int kSliceChunks = MT * 16 * kCPR;
   constexpr int kDma = (kSliceChunks + WPG * 64 - 1) / (WPG * 64);
-  constexpr int kDmaMin = kSliceChunks / (WPG * 64);   // direct loads per slice that every wavefront issues
+  static_assert(kSliceChunks % 64 == 0 && kSliceChunks >= 64, "a slice is a whole number of wavefront-wide loads");
   constexpr int kPatchRow = NW * 16 + 4;           // floats per padded row of the epilogue patch
   // steps per trip of the main loop: whole pairs of slices (buffers A, B) and whole turns of the weight ring, so
   // that both the buffer and the ring array of every step are known at compile time
@@ -121,6 +122,8 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
   // The weight fragments travel by direct global->LDS loads as well, into a ring of PF steps: one array per step (so
   // that the compiler can tell them apart), each wavefront using its own NW KB of every array.  A register prefetch
   // next to direct-to-LDS loads would make the compiler drain the load counter at each first use of a register.
+  // (Measured: fetching the weights into registers eight steps ahead instead, which doubles the bytes in flight per CU
+  // and keeps them out of LDS, is no faster at 144 rows: 222 against 218 us per step.)
   constexpr int kRing = WPG * NW * 64;
   __shared__ uint4 sW0[kRing], sW1[kRing], sW2[PF > 2 ? kRing : 1], sW3[PF > 3 ? kRing : 1], sW4[PF > 4 ? kRing : 1],
       sW5[PF > 5 ? kRing : 1];
@@ -173,8 +176,11 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
     const int kc = min(kc_want, nks - kKSteps);
 #pragma unroll
     for (int j = 0; j < kDma; ++j) {
-      const int q0 = (j * WPG + wave) * 64;        // wave-uniform
-      if (q0 < kSliceChunks) {
+      // wave-uniform.  A wavefront whose turn falls past the end loads the last 64 chunks once more (the same bytes to
+      // the same place as their owner): every wavefront then issues exactly kDma loads per slice, the loop has no
+      // branch, and the load counter can be waited on by number.
+      const int q0 = min((j * WPG + wave) * 64, kSliceChunks - 64);
+      {
         const int q = q0 + lane;
         const int row = q / kCPR, pc = q % kCPR;
         const int lc = pc ^ row_key(row);
@@ -225,7 +231,7 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
       // were requested, so they have landed once no more loads than that are outstanding.  Waiting by number here
       // (with an instruction between the wait and the read) also spares the compiler from inserting its own wait,
       // which with direct-to-LDS loads in flight is always a full drain.
-      __builtin_amdgcn_s_waitcnt(vmcnt_imm((PF - 1) * NW + (PF / kKSteps) * kDmaMin));
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm((PF - 1) * NW + (PF / kKSteps) * kDma));
       asm volatile("s_nop 0");
       __builtin_amdgcn_sched_barrier(0);
       uint4 bw[NW];
@@ -255,21 +261,23 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
     wg_barrier();
   };
 
-  for (int base = 0; base < nks; base += kUnroll) {
-    bool done = false;
+  // Whole trips run without a branch inside (the compiler's bookkeeping of the load counter degrades to full drains at
+  // the first use of a loaded register behind any control-flow merge that a shorter path could reach); the slices that
+  // are left after the last whole trip follow as straight-line code behind forward branches.
+  auto one_slice = [&](int kc, int p) {
+    request(kc + kKSteps, (p & 1) ? sA : sB);
+    __builtin_amdgcn_sched_barrier(0);
+    compute((p & 1) ? sB : sA, kc, (p * kKSteps) % PF);
+    hand_over();
+  };
+  int base = 0;
+  for (; base + kUnroll <= nks; base += kUnroll) {
 #pragma unroll
-    for (int p = 0; p < kUnroll / kKSteps; ++p) {
-      if (!done) {
-        const int kc = base + p * kKSteps;
-        request(kc + kKSteps, (p & 1) ? sA : sB);
-        __builtin_amdgcn_sched_barrier(0);
-        compute((p & 1) ? sB : sA, kc, (p * kKSteps) % PF);
-        hand_over();
-        done = kc + kKSteps >= nks;
-      }
-    }
-    if (done) break;
+    for (int p = 0; p < kUnroll / kKSteps; ++p) one_slice(base + p * kKSteps, p);
   }
+#pragma unroll
+  for (int p = 0; p < kUnroll / kKSteps - 1; ++p)
+    if (base + p * kKSteps < nks) one_slice(base + p * kKSteps, p);
   if (fs.part) {
     // Row statistics of this workgroup's column tile, from the accumulators: per row the maximum, its lowest column
     // and sum exp((z - max)/T), first per wavefront (NW*16 columns), then merged over the wavefronts; one partial per
@@ -392,7 +400,6 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
 // over its 8 wavefronts, so that even a 32000-column head yields thousands of wavefronts streaming W; the hidden
 // fragments are tiny and read straight from global memory (L2 resident).  The 8 partial tiles are summed through
 // LDS in a fixed order.
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 template <int PF>
 __global__ __launch_bounds__(512) void lmhead_bf16_skinny_kernel(const uint16_t* __restrict__ H, int M, int d,
                                                                  const uint4* __restrict__ Wp, int nks,
