@@ -42,7 +42,6 @@ __global__ __launch_bounds__(kDrawThreads) void accept_draw_kernel(StepArgs a, R
   __shared__ double s_pS[64];
   __shared__ int s_parg[64];
   int dv[kPerLane];
-  if (kDraw) load_tmap<kPerLane>(a.tmap, a.V_t, draw_first_id(grp, wave, lane), 64, dv);   // needed last, asked for first
 
   const int r0 = ro.v[b];
   const int k = ro.v[b + 1] - r0 - 1;
@@ -70,6 +69,9 @@ __global__ __launch_bounds__(kDrawThreads) void accept_draw_kernel(StepArgs a, R
   for (int row = wave; row <= k; row += kDrawWaves)
     merge_fused_row(a.fused.part, a.fused.nfine, r0 + row, invT, lane, s_pmx, s_pS, s_parg, row, lead, a.row_max, a.row_sum,
                     a.row_arg);
+  // The inverse map of this wavefront's ids is needed last (by the tile masses) and asked for here, behind the loads
+  // that the test waits for: loads return in issue order, and asked for first it held those back by its own latency.
+  if (kDraw) load_tmap<kPerLane>(a.tmap, a.V_t, draw_first_id(grp, wave, lane), 64, dv);
   __syncthreads();
   if (wave == kTestWave) {
     const FinalInfo fin = accept_wave(a, b, r0, k, r0 - b, T, Td, invT, invTd, sid, P, true, z_tok, s_pmx, s_pS, s_parg,
