@@ -103,6 +103,7 @@ int ot_verify_init(const ot_verify_config* cfg, ot_ctx** out) {
   c->nchd = ceil_div(cfg->V_d, kStatChunk);
   c->ntiles = ceil_div(cfg->V_t, kResidTile);
   hipError_t e = hipGetDevice(&c->device);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&c->n_cu, hipDeviceAttributeMultiprocessorCount, c->device);
   if (e != hipSuccess) { free_ctx(c); return fail_hip(e, "hipGetDevice"); }
   if (ot_static_scratch_prepare() != OT_OK) { free_ctx(c); return OT_ERR_HIP; }
 
@@ -117,11 +118,11 @@ int ot_verify_init(const ot_verify_config* cfg, ot_ctx** out) {
     const size_t nf = (size_t)(c->Vp / 256);
     ok = ok && dev_alloc(c, &c->fpart, R * nf);
   }
-  ok = ok && dev_alloc(c, &c->proposal, R);
   ok = ok && dev_alloc(c, &c->dpart_max, KQ * c->nchd) && dev_alloc(c, &c->dpart_sum, KQ * c->nchd) && dev_alloc(c, &c->dpart_arg, KQ * c->nchd);
   ok = ok && dev_alloc(c, &c->row_max, R) && dev_alloc(c, &c->row_sum, R) && dev_alloc(c, &c->row_arg, R);
   ok = ok && dev_alloc(c, &c->drow_max, KQ) && dev_alloc(c, &c->drow_sum, KQ) && dev_alloc(c, &c->drow_arg, KQ);
-  ok = ok && dev_alloc(c, &c->fin, Bm);
+  ok = ok && dev_alloc(c, &c->fin, Bm) && dev_alloc(c, &c->probe, Bm) &&
+       dev_alloc(c, &c->dpiece, KQ * otv::kDraftPieces);
   {
     char* rows = nullptr;
     ok = ok && dev_alloc(c, &rows, R * kLossRowBytes) && dev_alloc(c, &c->loss_tiles, R * c->ntiles);
@@ -195,7 +196,8 @@ static int step_impl(ot_ctx* ctx, ot_ngram_cache* cache, const ot_step_in* in, c
   a.row_max = ctx->row_max; a.row_sum = ctx->row_sum; a.row_arg = ctx->row_arg;
   a.drow_max = ctx->drow_max; a.drow_sum = ctx->drow_sum; a.drow_arg = ctx->drow_arg;
   a.fin = ctx->fin;
-  a.proposal = ctx->proposal;
+  a.probe = ctx->probe;
+  a.dpiece = ctx->dpiece;
   a.tile_r = ctx->tile_r; a.tile_p = ctx->tile_p; a.resid_count = ctx->resid_count;
   a.out = *o;
 
@@ -219,26 +221,27 @@ static int step_impl(ot_ctx* ctx, ot_ngram_cache* cache, const ot_step_in* in, c
       // Where its kernel supports it, the LM-head launch leaves per-tile softmax partials of the target rows (no second
       // pass over the logits) and hosts the draft side of the step in extra workgroups: what follows it is then only
       // the merge of those partials with the acceptance test, and the final draw.
-      const bool supported = lmhead_bf16_fused_partials(M, ctx->Vp) > 0 && in->B <= kFusedMaxB;
+      const bool supported = lmhead_bf16_draft_workers(M, ctx->Vp, in->B, K, ctx->n_cu) > 0 && K >= 1 && in->B <= kFusedMaxB;
       const bool host_it = supported && (ctx->draft_side == OT_DRAFT_SIDE_IN_LM_HEAD ||
                                          (ctx->draft_side == OT_DRAFT_SIDE_AUTO &&
-                                          lmhead_bf16_hosts_draft_side(M, ctx->d, ctx->Vp, in->B, K, ctx->V_d)));
-      const int nfine = host_it ? lmhead_bf16_fused_partials(M, ctx->Vp) : 0;
+                                          lmhead_bf16_hosts_draft_side(M, ctx->d, ctx->Vp, in->B, K, ctx->n_cu)));
+      const int nfine = host_it ? lmhead_bf16_fused_partials(M, ctx->Vp, ctx->n_cu) : 0;
       if (nfine > 0) {
         a.fused.row_off = in->row_off; a.fused.temperature = in->temperature; a.fused.B = in->B; a.fused.nfine = nfine;
         a.fused.part = ctx->fpart;
-        a.pre_translated = 1;
+        a.hosted = 1;
+        a.plan = make_piece_plan(lmhead_bf16_draft_workers(M, ctx->Vp, in->B, K, ctx->n_cu), K);
       }
       e = launch_lmhead_bf16(static_cast<const uint16_t*>(in->hidden), M, ctx->d, ctx->Wp, ctx->Kp, ctx->Vp, ctx->Z,
-                             ctx->V_t, a.ldz, ctx->zeros, &a.fused, a.pre_translated ? &a : nullptr, st);
+                             ctx->V_t, a.ldz, ctx->zeros, &a.fused, a.hosted ? &a : nullptr, ctx->n_cu, st);
     }
     else
       e = launch_lmhead_f32(static_cast<const float*>(in->hidden), M, ctx->d, ctx->Wf, ctx->Z, ctx->V_t, a.ldz, st);
   }
   OT_MARK(1);
-  if (e == hipSuccess && !a.pre_translated) e = launch_softmax_stats(a, st);
+  if (e == hipSuccess && !a.hosted) e = launch_softmax_stats(a, st);
   OT_MARK(2);
-  if (e == hipSuccess && !a.pre_translated) e = launch_translate_accept(a, st);
+  if (e == hipSuccess && !a.hosted) e = launch_translate_accept(a, st);
   OT_MARK(3);
   if (e == hipSuccess) e = launch_final_draw(a, in->row_off_host, st);
   OT_MARK(4);

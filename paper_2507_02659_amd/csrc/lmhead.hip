@@ -102,7 +102,8 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
                                                                     int n_wtiles, float* __restrict__ Z, int V_t,
                                                                     int64_t ldz, int vec_store,
                                                                     const uint16_t* __restrict__ zeros, int m_blocks,
-                                                                    FusedStats fs, int n_role, StepArgs ds) {
+                                                                    FusedStats fs, int n_front, int n_piece_jobs,
+                                                                    int helpers_look_up, StepArgs ds) {
   constexpr int kKSteps = KC / 32;                 // MFMA steps per slice
   constexpr int kCPR = KC / 8;                     // 16-byte chunks per slice row
   constexpr int kSliceChunks = MT * 16 * kCPR;
@@ -131,25 +132,149 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
   // and the exponent scale log2(e)/T of each row of the M-block
   __shared__ int32_t sRowOff[kFusedMaxB + 1];
   __shared__ float sTemp[kFusedMaxB + 1];
+  __shared__ float sTempDraft[kFusedMaxB + 1];       // the drafter's temperatures, staged only when they are given apart
   __shared__ float sScale[MT * 16];
   static_assert(WPG * 64 >= kFusedMaxB + 1, "one thread per sequence stages its row offset and temperature");
   static_assert((WPG & (WPG - 1)) == 0, "the mask below tells the compiler the range of the wavefront index");
   const int tid = threadIdx.x, wave = (tid >> 6) & (WPG - 1), lane = tid & 63;
-  // The first n_role workgroups of the launch do not multiply: they run the draft side of the step (softmax statistics
-  // of the draft rows, translation into the target vocabulary, parked proposals), which needs none of the logits, while
-  // the other workgroups stream the weights.  n_role is a multiple of 8, so the mapping below keeps its XCD.
-  if ((int)blockIdx.x < n_role) {
-    static_assert(sizeof(RoleLds) <= sizeof(sPatch), "the draft side's scratch fits into the epilogue patch");
-    draft_side_workgroup<uint16_t, WPG>(ds, blockIdx.x, n_role, tid, reinterpret_cast<RoleLds*>(&sPatch[0][0]));
-    return;
-  }
-  const int wg = (int)blockIdx.x - n_role;
+  // The first n_front workgroups of the launch (a multiple of 8) multiply nothing: they run the draft side (see below).
+  const int wg = (int)blockIdx.x - n_front;
   // Workgroup id -> (column tile, M-block).  Consecutive ids go round-robin to the 8 XCDs, each with its own L2; the
   // M-blocks of one column tile get ids that land on the same XCD back to back, so that when M needs several
   // blocks their weight streams coincide in that XCD's L2 and HBM is still read once.
   const int xcd = wg & 7, slot = wg >> 3;
   const int col_tile = (slot / m_blocks) * 8 + xcd, m_block = slot % m_blocks;
-  if (col_tile * WPG * NW >= n_wtiles * 4) return;    // padding of the id space (whole workgroup)
+  const int n_col_tiles = (n_wtiles * 4 + WPG * NW - 1) / (WPG * NW);
+  const bool hosts = n_piece_jobs > 0;               // this launch runs the draft side of the step (see below)
+  // stages the sequences' row offsets and temperatures in LDS (4-byte direct loads: lane i of a wavefront fills entry
+  // 64*wave + i); a wait for the loads and a barrier follow
+  auto stage_sequences = [&]() {
+    if (fs.part && wave * 64 <= fs.B) {
+      __builtin_amdgcn_global_load_lds((glb_ptr_t)(fs.row_off + min(tid, fs.B)), (lds_ptr_t)(sRowOff + wave * 64), 4, 0,
+                                       0);
+      __builtin_amdgcn_global_load_lds((glb_ptr_t)(fs.temperature + min(tid, fs.B - 1)), (lds_ptr_t)(sTemp + wave * 64),
+                                       4, 0, 0);
+      if (hosts && ds.draft_temperature)
+        __builtin_amdgcn_global_load_lds((glb_ptr_t)(ds.draft_temperature + min(tid, fs.B - 1)),
+                                         (lds_ptr_t)(sTempDraft + wave * 64), 4, 0, 0);
+    }
+  };
+  // The draft side of the step, the part that needs none of the logits, comes in two kinds of jobs.
+  // Piece job j: the softmax statistics (a3) of one piece of a draft row (see PiecePlan); at most one per multiplying
+  // workgroup, which asks for it in front of its first loads and reduces it while those land.  Lookup job b: what the
+  // drafted ids of sequence b look up (the drafted logit, the direct image, the n-gram table probes of every window),
+  // left as a ProbeRecord for the next launch, which walks the windows.
+  // All threads call a job (workgroup barriers inside).
+  // Every lane holds the row offsets and the drafter's temperatures of sequences lane, lane + 64, ...: the owner of a
+  // draft row (the last b with row_off[b] - b <= q, a monotone predicate) is then a count over ballots and its
+  // temperature one lane read, with no chain of dependent loads.  piece_request asks for these and for the first
+  // batch of the job's first row piece; piece_job (later, so that the loads overlap whatever is issued in between)
+  // reduces it and goes through the rest of the chunk.
+  constexpr int kSeqRegs = (kFusedMaxB + 64) / 64;
+  int seq_before[kSeqRegs];
+  float seq_temp[kSeqRegs];
+  RowFirstBatch<uint16_t, kPieceBatch> first_batch;
+  auto piece_request = [&](int job) {
+    const float* temps = ds.draft_temperature ? ds.draft_temperature : fs.temperature;
+#pragma unroll
+    for (int j = 0; j < kSeqRegs; ++j) {
+      const int b = min(64 * j + lane, fs.B - 1);
+      seq_before[j] = fs.row_off[b] - b;
+      seq_temp[j] = temps[b];
+    }
+    int q, i, e0, n;
+    ds.plan.locate(job, &q, &i);
+    PiecePlan::span(ds.V_d, ds.plan.pieces(q), i, &e0, &n);
+    workgroup_draft_piece_request<uint16_t, WPG>(ds, q, e0, n, tid, first_batch);
+  };
+  auto piece_job = [&](int job) {
+    float* st_mx = reinterpret_cast<float*>(&sPatch[0][0]);
+    int32_t* st_arg = reinterpret_cast<int32_t*>(st_mx + WPG);
+    double* st_S = reinterpret_cast<double*>(st_mx + 2 * WPG);
+    int q, i, e0, n;
+    ds.plan.locate(job, &q, &i);
+    bool first = true;
+    for (; q < ds.K; q += ds.plan.workers) {
+      PiecePlan::span(ds.V_d, ds.plan.pieces(q), i, &e0, &n);
+      int owner = -1;
+      float Td = 1.f;
+#pragma unroll
+      for (int j = 0; j < kSeqRegs; ++j) {
+        const bool before = 64 * j + lane < fs.B && seq_before[j] <= q;
+        owner += __popcll(__ballot(before));
+      }
+#pragma unroll
+      for (int j = 0; j < kSeqRegs; ++j) {
+        const float t = __shfl(seq_temp[j], owner & 63);
+        if ((owner >> 6) == j) Td = t;
+      }
+      DraftPiece* out = ds.dpiece + (int64_t)q * kDraftPieces + i;
+      if (first) workgroup_draft_piece<uint16_t, WPG, true>(ds, q, e0, n, Td, tid, st_mx, st_arg, st_S, out, &first_batch);
+      else workgroup_draft_piece<uint16_t, WPG>(ds, q, e0, n, Td, tid, st_mx, st_arg, st_S, out);
+      first = false;
+    }
+  };
+  auto lookup_job = [&](int b) {               // the sequences are staged in LDS
+    DraftLds* probe_lds = reinterpret_cast<DraftLds*>(&sPatch[0][0]);
+    static_assert(sizeof(DraftLds) <= sizeof(sPatch), "the lookups' scratch fits into the epilogue patch");
+    const int r0 = sRowOff[b], k = sRowOff[b + 1] - r0 - 1;
+    draft_lds_reset(probe_lds, tid);
+    __syncthreads();
+    fetch_ids_and_probe(ds, r0 - b, k, tid, WPG * 64, probe_lds);
+    __syncthreads();
+    ProbeRecord* rec = ds.probe + b;
+    if (tid < 64) { rec->hit[tid] = probe_lds->hit[tid]; rec->zq[tid] = probe_lds->zq[tid]; rec->dm[tid] = probe_lds->dm[tid]; }
+    if (tid == 0) rec->bad = probe_lds->bad;
+    __syncthreads();
+  };
+  // A workgroup with nothing to multiply takes the lookups of every n_helpers-th group of four sequences, 128 threads
+  // each: next to the other workgroups' weight streams every dependent load of a lookup takes several microseconds, and
+  // so the chains of loads of four sequences run side by side.  The sequences are staged first.
+  auto helper_lookups = [&](int helper, int n_helpers) {
+    stage_sequences();
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    wg_barrier();
+    constexpr int kAtOnce = WPG * 64 / 128;
+    static_assert(sizeof(DraftLds) * kAtOnce <= sizeof(sPatch), "the lookups' scratch fits into the epilogue patch");
+    const int slot = tid >> 7, g = tid & 127;
+    DraftLds* L = reinterpret_cast<DraftLds*>(&sPatch[0][0]) + slot;
+    for (int b0 = helper; b0 < fs.B; b0 += kAtOnce * n_helpers) {
+      const int b = b0 + slot * n_helpers;
+      const bool valid = b < fs.B;
+      const int r0 = valid ? sRowOff[b] : 0, k = valid ? sRowOff[b + 1] - r0 - 1 : 0;
+      if (valid) draft_lds_reset(L, g);
+      __syncthreads();
+      if (valid) fetch_ids_and_probe(ds, r0 - b, k, g, 128, L);
+      __syncthreads();
+      if (valid && g < 64) {
+        ProbeRecord* rec = ds.probe + b;
+        rec->hit[g] = L->hit[g]; rec->zq[g] = L->zq[g]; rec->dm[g] = L->dm[g];
+        if (g == 0) rec->bad = L->bad;
+      }
+      __syncthreads();
+    }
+  };
+  if (wg < 0) {
+    // Front workgroups: the whole draft side of a launch that is bound by the matrix cores (several M-blocks), where a
+    // piece in front of every multiplying workgroup's loop would add its time to each of them.  They start first and
+    // are done long before the launch ends; front workgroup h takes rows h, h + n_front, ... and its share of lookups.
+    const int h = (int)blockIdx.x;
+    if (h < n_piece_jobs) { piece_request(h); piece_job(h); }
+    helper_lookups(h, n_front);
+    return;
+  }
+  if (col_tile >= n_col_tiles) {
+    // Padding of the id space: a workgroup with nothing to multiply.  Where the launch has such workgroups and they can
+    // finish in time (the host decides), they take the sequences' lookups, on compute units that the multiplying
+    // workgroups leave idle.  (The draft rows stay with the multiplying workgroups: next to their saturating streams a
+    // workgroup that only reads was measured at about 10 GB/s however many loads it keeps in flight, so five of them
+    // cannot get through 8 MB of draft logits in time.)
+    if (helpers_look_up && hosts) {
+      const int n_pad_tiles = (n_col_tiles + 7) / 8 * 8 - n_col_tiles;
+      helper_lookups((col_tile - n_col_tiles) * m_blocks + m_block, n_pad_tiles * m_blocks);
+    }
+    return;
+  }
   const int t16_own = (col_tile * WPG + wave) * NW;   // first 16-column tile of this wavefront
   const bool active = t16_own < n_wtiles * 4;
   // A wavefront past the last tile (only in the last workgroup) multiplies the last tile again and stores nothing:
@@ -206,19 +331,21 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
                                        0, kWeightPolicy);
   };
 
+  // This workgroup's piece of the draft rows is asked for first: it is reduced while the first weight fragments and the
+  // hidden slice, asked for right behind it, land.  2 to 3 us that the launch which follows no longer has to wait for.
+  const int own_job = col_tile * m_blocks + m_block;
+  const bool has_job = n_front == 0 && own_job < n_piece_jobs;
+  if (has_job) piece_request(own_job);
   request(0, sA);
 #pragma unroll
   for (int s = 0; s < PF; ++s) fetch_w(min(s, nks - 1), s);
-  if (fs.part) {   // 4-byte direct loads: lane i of a wavefront fills entry 64*wave + i
-    if (wave * 64 <= fs.B) {
-      __builtin_amdgcn_global_load_lds((glb_ptr_t)(fs.row_off + min(tid, fs.B)), (lds_ptr_t)(sRowOff + wave * 64), 4, 0,
-                                       0);
-      __builtin_amdgcn_global_load_lds((glb_ptr_t)(fs.temperature + min(tid, fs.B - 1)), (lds_ptr_t)(sTemp + wave * 64),
-                                       4, 0, 0);
-    }
-  }
+  stage_sequences();
+  if (has_job) piece_job(own_job);
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
   wg_barrier();
+  // Without idle workgroups to take them, the lookups go to the multiplying workgroups as well, from the last one down.
+  if (hosts && !helpers_look_up && n_front == 0)
+    for (int b = n_col_tiles * m_blocks - 1 - own_job; b < fs.B; b += n_col_tiles * m_blocks) lookup_job(b);
 
   const int a_row = lane & 15, a_grp = lane >> 4;
   // one slice out of buffer hs; kc = its first step, s0 = ring array of that step (compile-time after unrolling)
@@ -283,13 +410,22 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
     // and sum exp((z - max)/T), first per wavefront (NW*16 columns), then merged over the wavefronts; one partial per
     // row and column tile goes to memory.  All LDS buffers of the main loop are free: every wavefront has passed the
     // barrier that followed its last slice (the weight ring may still receive the surplus refills; it is not used).
-    // The statistics scratch (3 x 4 bytes per lane and row tile) reuses the two hidden buffers; when those are too
-    // small for all row tiles at once the row tiles are taken in groups of kStatMT.
-    constexpr int kStatMT = MT * KC / (16 * WPG) < MT ? MT * KC / (16 * WPG) : MT;
+    // The statistics scratch (3 x 4 bytes per lane and row tile) reuses LDS of the main loop: either both hidden
+    // buffers (maxima and sums in the first, columns in the second), or, where that holds fewer row tiles at once, one
+    // hidden buffer each for the maxima and the sums and the first weight-ring array for the columns (the ring is
+    // drained first: the surplus refills past the end of K still land there).  When even that is too small for all row
+    // tiles at once the row tiles are taken in groups of kStatMT.
+    constexpr int kFitHidden = MT * KC / (16 * WPG), kFitSpread = MT * KC / (8 * WPG) < 4 * NW ? MT * KC / (8 * WPG) : 4 * NW;
+    constexpr bool kSpread = (kFitSpread < MT ? kFitSpread : MT) > (kFitHidden < MT ? kFitHidden : MT);
+    constexpr int kStatLim = kSpread ? (kFitSpread < MT ? kFitSpread : MT) : (kFitHidden < MT ? kFitHidden : MT);
+    constexpr int kStatMT = MT % kStatLim == 0 ? kStatLim : (MT % (kStatLim - 1) == 0 ? kStatLim - 1 : 1);
     static_assert(kStatMT >= 1 && MT % kStatMT == 0, "row tiles split evenly into statistics groups");
+    static_assert(sizeof(float) * WPG * kStatMT * 64 * (kSpread ? 1 : 2) <= sizeof(sA) &&
+                  sizeof(float) * WPG * kStatMT * 64 <= (kSpread ? sizeof(sW0) : sizeof(sB)), "the scratch fits");
     float* st_max = reinterpret_cast<float*>(sA);
-    float* st_sum = st_max + WPG * kStatMT * 64;
-    int32_t* st_arg = reinterpret_cast<int32_t*>(sB);
+    float* st_sum = kSpread ? reinterpret_cast<float*>(sB) : st_max + WPG * kStatMT * 64;
+    int32_t* st_arg = kSpread ? reinterpret_cast<int32_t*>(sW0) : reinterpret_cast<int32_t*>(sB);
+    if (kSpread) __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // before the barrier below
     for (int r = tid; r < MT * 16; r += WPG * 64) {
       const int row = min(row0 + r, M - 1);
       int lo = 0, hi = fs.B - 1;                    // sequence that owns the row: last b with row_off[b] <= row
@@ -496,12 +632,18 @@ __global__ __launch_bounds__(256) void lmhead_f32_kernel(const float* __restrict
     if (i < rows) Z[(int64_t)(m0 + i) * ldz + n] = acc[i];
 }
 
-// Workgroups of the launch that run the draft side: one per group of kRoleGroup sequences where 64 suffice, at least
-// 8, a multiple of 8 (the XCD mapping of the multiplying workgroups holds).  At the headline shape these fit into the
-// compute units that the last round of multiplying workgroups leaves idle (one workgroup per compute unit).
-int draft_side_workgroups(int B) {
-  const int groups = (B + kRoleGroup - 1) / kRoleGroup;
-  return std::min(64, std::max(8, (groups + 7) / 8 * 8));
+// Rows above which an M-block is split (16 rows per tile, at most 9 tiles in a block of the single-block shapes).
+constexpr int kSingleBlockRows = 144;
+
+// Rough duration of an LM-head launch: the weights stream at 6 TB/s or the product runs at 1 PFLOP/s, whichever is longer.
+double lmhead_launch_us(int M, int d, int Vp) { return std::max(2.0 * d * (double)Vp / 6.0e6, 2.0 * M * d * (double)Vp / 1.0e9); }
+
+// Front workgroups of a launch that hosts the draft side with several M-blocks: one per sequence or per 16 draft rows,
+// whichever is more; a multiple of 8 (the XCD mapping of the multiplying workgroups holds), 8 to 64.  0: one M-block,
+// where the multiplying workgroups take the draft side themselves.
+int lmhead_bf16_front_workgroups(int M, int B, int K) {
+  if (M <= kSingleBlockRows) return 0;
+  return std::min(64, std::max(8, ceil_div(std::max(B, ceil_div(K, 16)), 8) * 8));
 }
 
 template <int MT, int PF, int WPG, int KC, int NW, bool W_ONCE = false>
@@ -512,17 +654,31 @@ hipError_t launch_wide(const uint16_t* H, int M, int d, const uint16_t* Wp, int 
   const int m_blocks = ceil_div(M, MT * 16);
   const int col_tiles = ceil_div(n_wtiles * 4, WPG * NW);
   StepArgs ds{};
-  int n_role = 0;
+  int n_front = 0, n_piece_jobs = 0, helpers_look_up = 0;
+  const int padded_tiles = ceil_div(col_tiles, 8) * 8;
   if (draft_side && fs.part) {
     ds = *draft_side;
-    n_role = draft_side_workgroups(ds.B);
+    const PiecePlan& plan = ds.plan;
+    n_front = lmhead_bf16_front_workgroups(M, ds.B, ds.K);
+    const int workers = n_front > 0 ? n_front : col_tiles * m_blocks;
+    if (ds.K < 1 || plan.workers < 1 || plan.workers > workers || plan.base < 1 ||
+        plan.base + (plan.more > 0) > kDraftPieces || plan.more < 0 || plan.more > ds.K ||
+        (plan.workers < ds.K && (plan.base != 1 || plan.more != 0)))
+      return hipErrorInvalidValue;
+    n_piece_jobs = plan.jobs(ds.K);
+    // the workgroups that pad the id space take the sequences' lookups if they finish well inside the launch: about
+    // 60 us per four sequences (a chain of about six dependent loads next to the saturating weight streams) against
+    // the time the weights take to stream or the product to be formed
+    const int helpers = (padded_tiles - col_tiles) * m_blocks;
+    if (n_front == 0 && helpers > 0 && ceil_div(ds.B, 4 * helpers) * 60.0 <= 0.5 * lmhead_launch_us(M, d, Vp))
+      helpers_look_up = 1;
   }
-  dim3 grid(n_role + ceil_div(col_tiles, 8) * 8 * m_blocks), block(WPG * 64);
+  dim3 grid(n_front + padded_tiles * m_blocks), block(WPG * 64);
   const int vec_store = (ldz % 4 == 0) && (reinterpret_cast<uintptr_t>(Z) % 16 == 0);
   if (W_ONCE && m_blocks != 1) return hipErrorInvalidValue;
   hipLaunchKernelGGL((lmhead_bf16_wide_kernel<MT, PF, WPG, KC, NW, W_ONCE>), grid, block, 0, stream, H, M, d,
-                     reinterpret_cast<const uint4*>(Wp), nks, n_wtiles, Z, V_t, ldz, vec_store, zeros, m_blocks, fs, n_role,
-                     ds);
+                     reinterpret_cast<const uint4*>(Wp), nks, n_wtiles, Z, V_t, ldz, vec_store, zeros, m_blocks, fs,
+                     n_front, n_piece_jobs, helpers_look_up, ds);
   return hipGetLastError();
 }
 
@@ -536,33 +692,55 @@ hipError_t launch_pack_w_bf16(const uint16_t* W, int d, int V_t, uint16_t* Wp, i
   return hipGetLastError();
 }
 
-int lmhead_bf16_fused_partials(int M, int Vp) {
-  return M > 16 ? Vp / 256 : 0;      // the wide kernels own 256 columns per workgroup; the skinny kernel does not fuse
+// Columns per workgroup of the wide kernels.  A single M-block streams every weight once, bound by HBM, and what a
+// workgroup does outside its main loop (first loads, row statistics, stores: about 12 us) is time its CU does not
+// stream; with one workgroup per CU the launch runs in rounds, and a round costs its stream time whether or not all CUs
+// take part.  512 columns per workgroup halve the rounds where that lets the launch fit into fewer, e.g. one round of
+// 251 workgroups instead of two of 256-column ones on 256 CUs for a 128256-column head (measured: 175 against 196 us).
+int lmhead_bf16_tile_cols(int M, int Vp, int n_cu) {
+  if (M <= 16 || M > kSingleBlockRows || n_cu < 1) return 256;
+  const int tiles256 = Vp / 256, tiles512 = ceil_div(Vp, 512);
+  constexpr int kOutsideLoop = 40;                    // per round, in units of columns streamed
+  const int cost256 = ceil_div(tiles256, n_cu) * (256 + kOutsideLoop);
+  const int cost512 = ceil_div(tiles512, n_cu) * (512 + kOutsideLoop);
+  return cost512 < cost256 ? 512 : 256;
 }
 
-// Whether the LM-head launch should host the draft side (and leave the softmax partials): only when its few draft-side
-// workgroups finish well inside the time the weights take to stream.  Estimates: a draft-side workgroup reads about
-// 10 GB/s next to the saturating weight stream (measured at the headline shape: 1 MB in 100 us) and spends about 20 us
-// per group of sequences on dependent loads; the product streams 5.5 TB/s or runs 1 PFLOP/s, whichever takes longer.
-bool lmhead_bf16_hosts_draft_side(int M, int d, int Vp, int B, int K, int V_d) {
-  if (lmhead_bf16_fused_partials(M, Vp) == 0 || B < 1 || B > kFusedMaxB) return false;
-  const int n_role = draft_side_workgroups(B);
-  const double groups = std::ceil(std::ceil((double)B / n_role) / kRoleGroup);   // taken one after the other
-  const double per_wg = std::ceil((double)B / n_role);              // sequences a workgroup owns
-  const double bytes_per_group = (double)K / B * std::min<double>(kRoleGroup, per_wg) * V_d * 2.0;
-  const double role_us = groups * (20.0 + bytes_per_group / 10e3);
-  const double gemm_us = std::max(2.0 * d * Vp / 5.5e6, 2.0 * M * d * (double)Vp / 1.0e9);
-  return role_us <= gemm_us;
+int lmhead_bf16_fused_partials(int M, int Vp, int n_cu) {
+  if (M <= 16) return 0;             // the skinny kernel does not fuse
+  return ceil_div(Vp, lmhead_bf16_tile_cols(M, Vp, n_cu));
+}
+
+// Workgroups of launch_lmhead_bf16 that share the draft rows when the launch hosts the draft side: the multiplying
+// ones with a single M-block (their number: one per tile of columns), the front ones otherwise.  0: the shape leaves no
+// partials and hosts nothing.
+int lmhead_bf16_draft_workers(int M, int Vp, int B, int K, int n_cu) {
+  const int nfine = lmhead_bf16_fused_partials(M, Vp, n_cu);
+  if (nfine == 0) return 0;
+  return M > kSingleBlockRows ? lmhead_bf16_front_workgroups(M, B, K) : nfine;
+}
+
+// Whether the LM-head launch should host the draft side (the draft rows' statistics, the drafted ids' lookups, and the
+// target rows' softmax partials from its epilogue).  With a single M-block the launch is bound by the weight stream
+// and a multiplying workgroup's piece of a draft row costs it about the 3 us that it would otherwise wait for its first
+// loads: hosted when a workgroup gets at most two rows.  With several M-blocks front workgroups take the draft side:
+// hosted when they finish within half the launch (about 6 us a row, 60 us per four sequences).
+bool lmhead_bf16_hosts_draft_side(int M, int d, int Vp, int B, int K, int n_cu) {
+  if (B < 1 || B > kFusedMaxB || K < 1) return false;
+  const int workers = lmhead_bf16_draft_workers(M, Vp, B, K, n_cu);
+  if (workers == 0) return false;
+  if (M <= kSingleBlockRows) return K <= 2 * workers;
+  return ceil_div(K, workers) * 6.0 + ceil_div(B, 4 * workers) * 60.0 <= 0.5 * lmhead_launch_us(M, d, Vp);
 }
 
 hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
                               int64_t ldz, const uint16_t* zeros, const FusedStats* fused, const StepArgs* draft_side,
-                              hipStream_t stream) {
+                              int n_cu, hipStream_t stream) {
   if (M == 0) return hipSuccess;
   const int tiles = ceil_div(M, 16);
   FusedStats fs{};
   if (fused && fused->part) {
-    if (fused->nfine != lmhead_bf16_fused_partials(M, Vp) || fused->nfine == 0 || fused->B < 1 || fused->B > kFusedMaxB)
+    if (fused->nfine != lmhead_bf16_fused_partials(M, Vp, n_cu) || fused->nfine == 0 || fused->B < 1 || fused->B > kFusedMaxB)
       return hipErrorInvalidValue;
     fs = *fused;
   }
@@ -571,6 +749,13 @@ hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* W
     hipLaunchKernelGGL((lmhead_bf16_skinny_kernel<4>), dim3(n_wtiles), dim3(512), 0, stream, H, M, d,
                        reinterpret_cast<const uint4*>(Wp), nks, Z, V_t, ldz);
     return hipGetLastError();
+  }
+  if (tiles <= 9 && lmhead_bf16_tile_cols(M, Vp, n_cu) == 512) {
+    // wavefronts of 64 columns, hidden slices of 64 columns and a ring two (twice as long) steps deep: the same bytes
+    // in flight per CU as the 256-column shape
+    if (tiles <= 4) return launch_wide<4, 2, 8, 64, 4, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
+    if (tiles <= 6) return launch_wide<6, 2, 8, 64, 4, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
+    return launch_wide<9, 2, 8, 64, 4, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
   }
   if (tiles <= 2) return launch_wide<2, 4, 8, 128, 2, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
   if (tiles <= 4) return launch_wide<4, 4, 8, 128, 2, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);

@@ -27,7 +27,9 @@ struct ot_ctx {
   double *tpart_sum = nullptr, *dpart_sum = nullptr, *row_sum = nullptr, *drow_sum = nullptr;
   int32_t *tpart_arg = nullptr, *dpart_arg = nullptr, *row_arg = nullptr, *drow_arg = nullptr;
   otv::Partial* fpart = nullptr;      // [max_rows, Vp/256] softmax partials from the LM-head epilogue (bf16)
-  otv::RowProposal* proposal = nullptr;   // [max_rows] translated proposals parked between two kernels
+  int n_cu = 0;                       // compute units of the device
+  otv::DraftPiece* dpiece = nullptr;  // [max_K, kDraftPieces] pieces of the draft rows' statistics, as the probe records
+  otv::ProbeRecord* probe = nullptr;  // [max_batch] lookups of the drafted ids, between the LM-head launch and the next
   double *tile_r = nullptr, *tile_p = nullptr;
   int32_t* resid_count = nullptr;     // [max_batch] arrival counters of the residual launch, zero between launches
   otv::FinalInfo* fin = nullptr;

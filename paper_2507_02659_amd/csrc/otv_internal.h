@@ -43,6 +43,17 @@ struct CacheTable {
 constexpr int kCacheLogCap = 4096;    // uses the device can log between two maintenance calls of a cache
 constexpr int kCachePatchCap = 1024;  // slots that travel as a packed patch; more than that uploads the arrays whole
 
+// What the drafted ids of one sequence look up, none of which needs the target's logits: per draft position the longest
+// n-gram cache hit that starts there, the drafted id's own logit and its direct image.  Written by a workgroup of the
+// LM-head launch, read by the launch that follows it (which walks the window, Eq. 1, and tests acceptance).
+struct ProbeRecord {
+  unsigned long long hit[64];   // (length << 60) | (slot << 32) | target, 0 = no hit
+  float zq[64];                 // draft logit of the drafted id
+  int32_t dm[64];               // direct image of the drafted id, or -1
+  int32_t bad;                  // a drafted id was outside [0, V_d)
+  int32_t pad[3];
+};
+
 // ------------------------------------------------------------------------------------------------ per-step view
 // What the final-token kernels need to know about sequence b; written by the translate-and-accept kernel.
 struct FinalInfo {
@@ -60,23 +71,6 @@ struct FinalInfo {
   // p(v) = exp((z_v - mx) * invT) * invS at the final row; q_s(d) = exp((zq_d - mxq) * invTd) * invSq at draft row drow
   double mx, invT, invS, mxq, invTd, invSq;
 };
-
-// One mapped position of a translated proposal, parked in memory between the kernel that translates (it needs only the
-// drafter's side of the step) and the kernel that tests acceptance (it needs the target's logits).  Entry
-// row_off[b] + j belongs to mapped position j of sequence b; j == n_mapped is filled when the proposal was cut by an
-// untranslatable id (its `start` is that id's draft position).
-struct RowProposal {
-  int32_t t;             // target id t_j, or -1 beyond the proposal
-  int32_t start, len;    // draft positions covered
-  int32_t t_pre;         // direct image of the draft id at `start` (Eq. 2, prefix case), or -1
-  int32_t argq;          // argmax of the draft row at `start`
-  float mxq;             // maximum of that row
-  double lq;             // log q'(t_j): sum of the sub-tokens' log-probabilities (Eq. 1)
-  double lq_first;       // log q(d) of the draft id at `start`
-  double Sq;             // sum of exponentials of that row
-  int32_t pad[4];
-};
-static_assert(sizeof(RowProposal) == 64, "one record per 64 bytes");
 
 // Softmax partial of one row over one column tile: maximum, its lowest column, sum of exp((z - mx) / T).
 struct alignas(16) Partial {
@@ -96,6 +90,43 @@ struct FusedStats {
   int32_t nfine;                     // partials per row (row stride of `part`)
   Partial* part;                     // [M, nfine]
 };
+
+// Softmax statistics of one piece of a draft row: (maximum, lowest index of it within the row, sum of
+// exp((x - maximum) / T_d)).  The LM-head launch shares the K draft rows out over `workers` of its workgroups, one job
+// each: the first `more` rows are cut into `base + 1` equal pieces (whole 16-byte vectors), the others into `base`
+// (at most kDraftPieces), and the launch that follows merges a row's pieces in ascending order.  With fewer workers
+// than rows a job takes whole rows, every `workers`-th.
+constexpr int kDraftPieces = 3;
+struct DraftPiece { float mx; int32_t arg; double sum; };
+static_assert(sizeof(DraftPiece) == 16, "one 16-byte record");
+struct PiecePlan {
+  int32_t workers, base, more;
+  __host__ __device__ int pieces(int q) const { return q < more ? base + 1 : base; }
+  __host__ __device__ int jobs(int K) const {
+    const int64_t all = (int64_t)more * (base + 1) + (int64_t)(K - more) * base;
+    return (int)(all < workers ? all : workers);
+  }
+  // job -> (row, piece index); rows q + workers, q + 2 workers, ... follow when workers < K (then base == 1, more == 0)
+  __host__ __device__ void locate(int job, int* q, int* i) const {
+    const int split = more * (base + 1);
+    if (job < split) { *q = job / (base + 1); *i = job % (base + 1); }
+    else { *q = more + (job - split) / base; *i = (job - split) % base; }
+  }
+  // elements [e0, e0 + n) of a V-element row that piece i of P covers (n <= 0: nothing)
+  __host__ __device__ static void span(int V, int P, int i, int* e0, int* n) {
+    const int len = ((V + P - 1) / P + 7) / 8 * 8;
+    *e0 = i * len;
+    *n = (V - *e0 < len ? V - *e0 : len);
+  }
+};
+inline PiecePlan make_piece_plan(int workers, int K) {
+  PiecePlan p{workers, 1, 0};
+  if (workers >= K && K > 0) {
+    p.base = workers / K < kDraftPieces ? workers / K : kDraftPieces;
+    p.more = p.base < kDraftPieces ? (workers - p.base * K < K ? workers - p.base * K : K) : 0;
+  }
+  return p;
+}
 
 struct StepArgs {
   // problem
@@ -122,9 +153,11 @@ struct StepArgs {
   float* dpart_max; double* dpart_sum; int32_t* dpart_arg;   // [K, nchd]
   float* row_max; double* row_sum; int32_t* row_arg;         // [M]
   float* drow_max; double* drow_sum; int32_t* drow_arg;      // [K]
-  RowProposal* proposal; // [M] written by the draft side when it runs apart from the acceptance test
-  int32_t pre_translated; // the draft side has already run (inside the LM-head launch): `proposal`, drow_* and the
-                         // translation outputs are final; the acceptance kernel only merges the LM head's partials
+  DraftPiece* dpiece;    // [K, kDraftPieces] statistics of the pieces of the draft rows, left by the LM-head launch
+  PiecePlan plan;        // how the LM-head launch shared out the draft rows
+  ProbeRecord* probe;    // [B] what the drafted ids of each sequence look up (see ProbeRecord), left by the LM-head launch
+  int32_t hosted;        // the LM-head launch left the target rows' softmax partials (`fused`) and the draft rows'
+                         // statistics (drow_*): one launch follows it, which translates, tests and draws
   FinalInfo* fin;        // [B]
   int32_t ntiles;        // residual tiles per row
   double* tile_r; double* tile_p;                            // [B, ntiles]
@@ -138,22 +171,25 @@ struct StepArgs {
 hipError_t launch_pack_w_bf16(const uint16_t* W, int d, int V_t, uint16_t* Wp, int Kp, int Vp, hipStream_t stream);
 // Partials per row that launch_lmhead_bf16 emits for M rows of a Vp-column (padded) head; 0: that shape runs a
 // kernel without the fused statistics.
-int lmhead_bf16_fused_partials(int M, int Vp);
+// (n_cu = compute units of the device: the column width of a workgroup is chosen so that the launch takes few rounds.)
+int lmhead_bf16_fused_partials(int M, int Vp, int n_cu);
 // Whether a step of this shape lets the LM-head launch host the draft side and emit the partials (else the step runs
 // the statistics and the translation as launches of their own).
-bool lmhead_bf16_hosts_draft_side(int M, int d, int Vp, int B, int K, int V_d);
+bool lmhead_bf16_hosts_draft_side(int M, int d, int Vp, int B, int K, int n_cu);
+// workgroups of launch_lmhead_bf16 that share the draft rows (0: that shape leaves no partials and hosts nothing)
+int lmhead_bf16_draft_workers(int M, int Vp, int B, int K, int n_cu);
 // `fused` may be nullptr or have part == nullptr (no statistics); otherwise fused->nfine must be
-// lmhead_bf16_fused_partials(M, Vp) > 0 and fused->B <= kFusedMaxB.  With fused statistics and `draft_side` not
-// nullptr, extra workgroups of the same launch run the draft side of the step (draft row statistics, translation,
-// parked proposals: everything of *draft_side that does not need the logits), hidden behind the weight stream.
+// lmhead_bf16_fused_partials(M, Vp, n_cu) > 0 and fused->B <= kFusedMaxB.  With fused statistics and `draft_side` not
+// nullptr, the workgroups of the launch also compute the softmax statistics of the draft rows of *draft_side (one row
+// each, before their main loop) into its drow_* arrays.
 hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
                               int64_t ldz, const uint16_t* zeros, const FusedStats* fused, const StepArgs* draft_side,
-                              hipStream_t stream);
+                              int n_cu, hipStream_t stream);
 hipError_t launch_lmhead_f32(const float* H, int M, int d, const float* W, float* Z, int V_t, int64_t ldz,
                              hipStream_t stream);
 hipError_t launch_softmax_stats(const StepArgs& a, hipStream_t stream);
 hipError_t launch_translate_accept(const StepArgs& a, hipStream_t stream);
-// acceptance test (when the draft side ran inside the LM-head launch) and the draw of the final tokens
+// translation and acceptance test (when the LM-head launch hosted the draft side) and the draw of the final tokens
 hipError_t launch_final_draw(const StepArgs& a, const int32_t* row_off_host, hipStream_t stream);
 
 }  // namespace otv

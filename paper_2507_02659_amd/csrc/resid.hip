@@ -37,6 +37,7 @@ __global__ __launch_bounds__(kDrawThreads) void accept_draw_kernel(StepArgs a, R
   const int wave = tid >> 6, lane = tid & 63;
   extern __shared__ double s_tiles[];
   __shared__ DrawLds s_draw;
+  __shared__ DraftLds s_d;
   __shared__ FinalInfo s_fin;
   __shared__ float s_pmx[64];
   __shared__ double s_pS[64];
@@ -53,17 +54,36 @@ __global__ __launch_bounds__(kDrawThreads) void accept_draw_kernel(StepArgs a, R
   const bool lead = grp == 0;               // the group that writes the test's outputs and the row statistics
   if (!(T > 0.f) && !lead) return;          // a greedy sequence draws nothing: its other groups have nothing to do
 
-  // the proposal is parked in memory; its loads go out first so that the gather of z[t_j] follows them early and is
-  // under way while the partials are merged
+  // The LM-head launch left what the drafted ids look up (ProbeRecord) and the draft rows' statistics.  The last
+  // wavefront fetches them (one load of each array per lane), walks the window (Eq. 1) and asks for the logits of the
+  // proposed tokens, all on its own, while the other wavefronts merge the softmax partials of the target rows; the
+  // translation is thus repeated by every tile group of the sequence, and the lead group writes its outputs and the
+  // cache's use statistics.
+  const int q0 = r0 - b;
+  constexpr int kTestWave = kDrawWaves - 1;   // runs the walk and the test
   LaneProposal P;
   P.t = -1; P.start = -1; P.L = 0; P.lq = 0.0; P.t_pre = -1; P.argq = -1; P.mxq = 0.f; P.Sq = 1.0; P.lq_first = 0.0;
   P.m = 0; P.flags = 0;
   float z_tok = 0.f;
-  constexpr int kTestWave = kDrawWaves - 1;   // runs the test; with up to 15 target rows it has no row to merge
   if (wave == kTestWave) {
-    if (lane <= k) fetch_proposal(a.proposal + r0 + lane, &P);
-    P.m = a.out.n_mapped[b];
-    P.flags = a.out.flags[b];
+    const ProbeRecord* rec = a.probe + b;
+    s_d.hit[lane] = rec->hit[lane]; s_d.zq[lane] = rec->zq[lane]; s_d.dm[lane] = rec->dm[lane];
+    if (lane < k) {
+      float mxq; double Sq; int argq;
+      merge_draft_pieces(a, q0 + lane, Td, &mxq, &Sq, &argq);
+      s_d.qmx[lane] = mxq; s_d.qS[lane] = Sq; s_d.qarg[lane] = argq;
+      if (lead) { a.drow_max[q0 + lane] = mxq; a.drow_sum[q0 + lane] = Sq; a.drow_arg[q0 + lane] = argq; }
+    }
+    const int bad = rec->bad;               // wavefront-uniform
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    if (bad) {
+      if (lead) translate_bad_sequence(a, b, r0, k, lane);
+      P.flags = OT_FLAG_BAD_ID;
+    } else {
+      translate_walk(a, b, r0, k, q0, Td, invTd, lane, &s_d, &P, lead);
+    }
     if (!(P.flags & OT_FLAG_BAD_ID) && lane < P.m && T > 0.f) z_tok = a.Z[(int64_t)(r0 + lane) * a.ldz + P.t];
   }
   for (int row = wave; row <= k; row += kDrawWaves)
@@ -74,8 +94,7 @@ __global__ __launch_bounds__(kDrawThreads) void accept_draw_kernel(StepArgs a, R
   if (kDraw) load_tmap<kPerLane>(a.tmap, a.V_t, draw_first_id(grp, wave, lane), 64, dv);
   __syncthreads();
   if (wave == kTestWave) {
-    const FinalInfo fin = accept_wave(a, b, r0, k, r0 - b, T, Td, invT, invTd, sid, P, true, z_tok, s_pmx, s_pS, s_parg,
-                                      lane, lead);
+    const FinalInfo fin = accept_wave(a, b, r0, k, q0, T, Td, invT, invTd, sid, P, true, z_tok, s_pmx, s_pS, s_parg, lane, lead);
     if (lane == 0) s_fin = fin;
   }
   if (!kDraw) {
@@ -90,13 +109,13 @@ __global__ __launch_bounds__(kDrawThreads) void accept_draw_kernel(StepArgs a, R
 
 }  // namespace
 
-// pre_translated: the LM-head launch left the parked proposals and its softmax partials (then B <= kFusedMaxB and
+// hosted: the LM-head launch left its softmax partials and the draft rows' statistics (then B <= kFusedMaxB and
 // row_off_host holds the B + 1 row offsets); otherwise a.fin is filled.
 hipError_t launch_final_draw(const StepArgs& a, const int32_t* row_off_host, hipStream_t stream) {
   if (a.B == 0) return hipSuccess;
   const dim3 grid(ceil_div(a.ntiles, kGroupTiles), a.B), block(kDrawThreads);
   const size_t lds = 2 * (size_t)a.ntiles * sizeof(double);
-  if (a.pre_translated) {
+  if (a.hosted) {
     if (a.B > kFusedMaxB) return hipErrorInvalidValue;
     RowOffsets ro;
     for (int b = 0; b <= kFusedMaxB; ++b) ro.v[b] = row_off_host[b <= a.B ? b : a.B];

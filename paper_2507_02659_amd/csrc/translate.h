@@ -46,7 +46,7 @@ struct LaneProposal {
 
 // Probe of one key held in registers (fully unrolled so that `ids` never has to live in scratch memory).
 // Returns the slot index of the entry, or -1.
-__device__ inline int cache_lookup(const CacheTable& C, const int32_t (&ids)[OT_MAX_NGRAM_LEN], int L) {
+__device__ __forceinline__ int cache_lookup(const CacheTable& C, const int32_t (&ids)[OT_MAX_NGRAM_LEN], int L) {
   uint32_t h = 0x9E3779B9u ^ (uint32_t)L;                  // same mixing as hash_ngram()
 #pragma unroll
   for (int i = 0; i < OT_MAX_NGRAM_LEN; ++i) {
@@ -75,7 +75,7 @@ __device__ inline int cache_lookup(const CacheTable& C, const int32_t (&ids)[OT_
   return -1;
 }
 
-__device__ inline void draft_lds_reset(DraftLds* L, int g) {
+__device__ __forceinline__ void draft_lds_reset(DraftLds* L, int g) {
   if (g == 0) L->bad = 0;
   if (g < 64) { L->hit[g] = 0ull; L->dm[g] = -1; }
 }
@@ -83,7 +83,7 @@ __device__ inline void draft_lds_reset(DraftLds* L, int g) {
 // Thread g of n: range check, drafted logit and direct image of the drafted positions; every window (s, len) of the
 // drafted ids against the n-gram table, the longest hit per start wins.  draft_lds_reset and a barrier come before,
 // a barrier after.
-__device__ inline void fetch_ids_and_probe(const StepArgs& a, int q0, int k, int g, int n, DraftLds* L) {
+__device__ __forceinline__ void fetch_ids_and_probe(const StepArgs& a, int q0, int k, int g, int n, DraftLds* L) {
   for (int i = g; i < k; i += n) {
     const int d = a.draft_ids[q0 + i];
     if (d < 0 || d >= a.V_d) {
@@ -168,9 +168,26 @@ struct RunStat {
 // maximum moves); the 64 lanes are merged at the end by shuffles in a fixed order.  Sums of one vector are formed in
 // binary32, everything above that in binary64.  Rows that do not start on a 16-byte boundary, and the last V % kVec
 // elements of the others, are read element by element.  All lanes return the row's statistics.
+// kFirst: the first batch was requested earlier (row_first_batch_load with the same x and V) and is taken from `first`.
+template <typename T, int kBatch> struct RowFirstBatch { typename RowVec<T>::Raw raw[kBatch]; };
+
 template <typename T, int kBatch>
-__device__ inline void wave_row_stats(const T* __restrict__ x, int V, float scale, int lane, float* out_max,
-                                      int* out_arg, double* out_sum) {
+__device__ __forceinline__ void row_first_batch_load(const T* __restrict__ x, int V, int lane,
+                                                     RowFirstBatch<T, kBatch>& first) {
+  constexpr int kVec = RowVec<T>::kVec;
+  const bool aligned = (reinterpret_cast<uintptr_t>(x) % 16) == 0;
+  const int n_vec = aligned && V > 0 ? V / kVec : 0;
+#pragma unroll
+  for (int j = 0; j < kBatch; ++j) {
+    const int at = j * 64 + lane;
+    first.raw[j] = at < n_vec ? RowVec<T>::load(x + (int64_t)at * kVec) : RowVec<T>::lowest();
+  }
+}
+
+template <typename T, int kBatch, bool kFirst = false>
+__device__ __forceinline__ void wave_row_stats(const T* __restrict__ x, int V, float scale, int lane, float* out_max,
+                                               int* out_arg, double* out_sum,
+                                               const RowFirstBatch<T, kBatch>* first = nullptr) {
   constexpr int kVec = RowVec<T>::kVec;
   typedef typename RowVec<T>::Raw Raw;
   const bool aligned = (reinterpret_cast<uintptr_t>(x) % 16) == 0;
@@ -181,12 +198,14 @@ __device__ inline void wave_row_stats(const T* __restrict__ x, int V, float scal
 #pragma unroll
     for (int j = 0; j < kBatch; ++j) {
       const int at = base + j * 64 + lane;
-      raw[j] = at < n_vec ? RowVec<T>::load(x + (int64_t)at * kVec) : RowVec<T>::lowest();
+      if (kFirst && base == 0) raw[j] = first->raw[j];
+      else raw[j] = at < n_vec ? RowVec<T>::load(x + (int64_t)at * kVec) : RowVec<T>::lowest();
     }
     float bm = -INFINITY;
     int bi = 0x7FFFFFFF;
 #pragma unroll
     for (int j = 0; j < kBatch; ++j) {
+      if (base + j * 64 >= n_vec) break;        // wavefront-uniform: the remaining vectors of the batch are empty
       float v[kVec];
       RowVec<T>::unpack(raw[j], v);
 #pragma unroll
@@ -197,6 +216,7 @@ __device__ inline void wave_row_stats(const T* __restrict__ x, int V, float scal
     if (r.mx != -INFINITY) {
 #pragma unroll
       for (int j = 0; j < kBatch; ++j) {
+        if (base + j * 64 >= n_vec) break;
         // the vector is unpacked again rather than kept unpacked since the first pass (8 registers instead of 4 each)
         asm volatile("" : "+v"(raw[j].x), "+v"(raw[j].y), "+v"(raw[j].z), "+v"(raw[j].w));
         float v[kVec];
@@ -229,10 +249,11 @@ __device__ inline void wave_row_stats(const T* __restrict__ x, int V, float scal
 
 // ---------------------------------------------------------------------------------------------- the walk
 // One wavefront (lane = threadIdx within it), after the barrier that publishes L: forms log q_i(d_i), walks the window
-// and returns mapped position `lane` in P.  Writes the translation's outputs (n_mapped, hits_proposed, flags;
-// mapped_ids, span_start, span_len, q_tok of the sequence's rows) and the use statistics of the cache entries.
+// and returns mapped position `lane` in P.  With `lead` it also writes the translation's outputs (n_mapped,
+// hits_proposed, flags; mapped_ids, span_start, span_len, q_tok of the sequence's rows) and the use statistics of the
+// cache entries; where several workgroups walk the same sequence exactly one of them leads.
 __device__ inline void translate_walk(const StepArgs& a, int b, int r0, int k, int q0, float Td, double invTd, int lane,
-                                      DraftLds* L, LaneProposal* P) {
+                                      DraftLds* L, LaneProposal* P, bool lead = true) {
   if (lane < k) {
     double lq;
     if (Td > 0.f) lq = ((double)L->zq[lane] - (double)L->qmx[lane]) * invTd - log(L->qS[lane]);
@@ -277,7 +298,7 @@ __device__ inline void translate_walk(const StepArgs& a, int b, int r0, int k, i
   P->lq = lane < m ? lq_j : 0.0;
   P->m = m; P->flags = flags;
   const int hits = __popcll(__ballot(lane < m && P->L > 1));
-  if (lane < m && P->L > 1) {
+  if (lead && lane < m && P->L > 1) {
     // use statistics of the entry (Appendix, cache eviction): one more use, last used now
     atomicAdd(&a.cache.uses[slot_j], 1u);
     a.cache.last_used[slot_j] = a.cache.clock;
@@ -292,12 +313,12 @@ __device__ inline void translate_walk(const StepArgs& a, int b, int r0, int k, i
     P->lq_first = L->logq[s_fin];
     if (lane == m) P->start = s_fin;
   }
-  if (lane == 0) {
+  if (lead && lane == 0) {
     a.out.n_mapped[b] = m;
     a.out.hits_proposed[b] = hits;
     a.out.flags[b] = flags;
   }
-  if (lane <= k) {
+  if (lead && lane <= k) {
     a.out.mapped_ids[r0 + lane] = P->t;
     a.out.span_start[r0 + lane] = lane < m ? start_j : -1;
     a.out.span_len[r0 + lane] = P->L;
@@ -314,94 +335,88 @@ __device__ inline void translate_bad_sequence(const StepArgs& a, int b, int r0, 
   if (lane == 0) { a.out.n_mapped[b] = 0; a.out.hits_proposed[b] = 0; a.out.flags[b] = OT_FLAG_BAD_ID; }
 }
 
-__device__ inline void park_proposal(RowProposal* rec, const LaneProposal& P) {
-  RowProposal r;
-  r.t = P.t; r.start = P.start; r.len = P.L; r.t_pre = P.t_pre; r.argq = P.argq; r.mxq = P.mxq;
-  r.lq = P.lq; r.lq_first = P.lq_first; r.Sq = P.Sq;
-  r.pad[0] = 0; r.pad[1] = 0;
-  *rec = r;
-}
-
-__device__ inline void fetch_proposal(const RowProposal* rec, LaneProposal* P) {
-  const RowProposal r = *rec;
-  P->t = r.t; P->start = r.start; P->L = r.len; P->t_pre = r.t_pre; P->argq = r.argq; P->mxq = r.mxq;
-  P->lq = r.lq; P->lq_first = r.lq_first; P->Sq = r.Sq;
-}
-
-// The draft side of a share of the batch by one workgroup of kWaves >= kRoleGroup wavefronts (all threads call it; it contains workgroup
-// barriers).  Workgroup wg of n_wg owns the sequences b = wg, wg + n_wg, ..; it takes them kRoleGroup at a time so that
-// their dependent loads (row offsets -> drafted ids -> table slots) are in flight side by side: the drafted positions
-// and the probe windows of the whole group are spread over all threads, the group's draft rows over the wavefronts,
-// and wavefront s then walks sequence s of the group and parks one RowProposal per row of it.
-constexpr int kRoleGroup = 4;
-struct RoleLds {
-  DraftLds seq[kRoleGroup];
-  int32_t b[kRoleGroup], r0[kRoleGroup], k[kRoleGroup];   // k < 0: the slot is unused
-  float Td[kRoleGroup];
-};
-
+// Softmax statistics of elements [e0, e0 + n) of draft row q by one workgroup of kWaves wavefronts (all threads call it;
+// it contains workgroup barriers): every wavefront takes a contiguous slice, the slices are merged through LDS in
+// ascending order (of equal maxima the lowest index is kept, the sums are added in one fixed order), thread 0 writes the
+// record.  s_mx / s_arg / s_S: kWaves LDS words each.
+constexpr int kPieceBatch = 8;
+// the slice of elements [e0, e0 + n) of draft row q that wavefront `wave` of kWaves takes: whole 16-byte vectors
 template <typename TD, int kWaves>
-__device__ inline void draft_side_workgroup(const StepArgs& a, int wg, int n_wg, int tid, RoleLds* R) {
-  static_assert(kWaves >= kRoleGroup, "one walking wavefront per sequence of a group");
+__device__ __forceinline__ const TD* piece_wave_slice(const StepArgs& a, int q, int e0, int n, int wave, int* lo, int* n_own) {
+  constexpr int kVec = RowVec<TD>::kVec;
+  const int slice = ((n + kWaves - 1) / kWaves + kVec - 1) / kVec * kVec;
+  *lo = wave * slice;
+  *n_own = min(slice, n - *lo);
+  return static_cast<const TD*>(a.draft_logits) + (int64_t)q * a.V_d + e0 + *lo;
+}
+
+// requests the first batch of this wavefront's slice, for a later workgroup_draft_piece<.., true> of the same piece
+template <typename TD, int kWaves>
+__device__ __forceinline__ void workgroup_draft_piece_request(const StepArgs& a, int q, int e0, int n, int tid,
+                                                              RowFirstBatch<TD, kPieceBatch>& first) {
+  int lo, n_own;
+  const TD* x = piece_wave_slice<TD, kWaves>(a, q, e0, n, tid >> 6, &lo, &n_own);
+  row_first_batch_load<TD, kPieceBatch>(x, n_own, tid & 63, first);
+}
+
+template <typename TD, int kWaves, bool kFirst = false>
+__device__ __forceinline__ void workgroup_draft_piece(const StepArgs& a, int q, int e0, int n, float Td, int tid,
+                                                      float* s_mx, int32_t* s_arg, double* s_S, DraftPiece* out,
+                                                      const RowFirstBatch<TD, kPieceBatch>* first = nullptr) {
   const int wave = tid >> 6, lane = tid & 63;
-  for (int b0 = wg; b0 < a.B; b0 += kRoleGroup * n_wg) {
-    __syncthreads();                             // the previous group's walks have finished with R
-    if (tid < kRoleGroup) {
-      const int b = b0 + tid * n_wg;
-      int r0 = 0, k = -1;
-      float Td = 1.f;
-      if (b < a.B) {
-        r0 = a.row_off[b];
-        k = a.row_off[b + 1] - r0 - 1;
-        Td = a.draft_temperature ? a.draft_temperature[b] : a.temperature[b];
-      }
-      R->b[tid] = b; R->r0[tid] = r0; R->k[tid] = k; R->Td[tid] = Td;
-    }
-    if (tid < kRoleGroup * 64) draft_lds_reset(&R->seq[tid >> 6], lane);
-    __syncthreads();
-    // ids, drafted logits, direct images and table probes of the whole group: task t of sequence s is handled by
-    // thread (t + offset of s) modulo the workgroup, so that a small group still spreads over different wavefronts
-    int first[kRoleGroup + 1];
-    first[0] = 0;
-#pragma unroll
-    for (int s = 0; s < kRoleGroup; ++s) first[s + 1] = first[s] + max(R->k[s], 0);
-#pragma unroll
-    for (int s = 0; s < kRoleGroup; ++s) {
-      const int k = R->k[s];
-      if (k > 0) {
-        const int g = (tid + kWaves * 64 - (s * 128) % (kWaves * 64)) % (kWaves * 64);
-        fetch_ids_and_probe(a, R->r0[s] - R->b[s], k, g, kWaves * 64, &R->seq[s]);
-      }
-    }
-    // draft rows of the group, one wavefront per row
-    for (int f = wave; f < first[kRoleGroup]; f += kWaves) {
-      int s = 0;
-#pragma unroll
-      for (int t = 1; t < kRoleGroup; ++t) s += (f >= first[t]) ? 1 : 0;
-      const int i = f - first[s];
-      const int q = R->r0[s] - R->b[s] + i;
-      const float Td = R->Td[s];
-      const float scale = Td > 0.f ? kLog2eF / Td : kLog2eF;
-      float mx; int arg; double S;
-      wave_row_stats<TD, 32>(static_cast<const TD*>(a.draft_logits) + (int64_t)q * a.V_d, a.V_d, scale, lane, &mx, &arg, &S);
-      if (lane == 0) {
-        R->seq[s].qmx[i] = mx; R->seq[s].qS[i] = S; R->seq[s].qarg[i] = arg;
-        a.drow_max[q] = mx; a.drow_sum[q] = S; a.drow_arg[q] = arg;
-      }
-    }
-    __syncthreads();
-    if (wave < kRoleGroup && R->k[wave] >= 0) {
-      const int s = wave, b = R->b[s], r0 = R->r0[s], k = R->k[s];
-      if (R->seq[s].bad) {
-        translate_bad_sequence(a, b, r0, k, lane);
-      } else {
-        const float Td = R->Td[s];
-        LaneProposal P;
-        translate_walk(a, b, r0, k, r0 - b, Td, Td > 0.f ? 1.0 / (double)Td : 1.0, lane, &R->seq[s], &P);
-        if (lane <= k) park_proposal(a.proposal + r0 + lane, P);
-      }
-    }
+  int lo, n_own;
+  const TD* x = piece_wave_slice<TD, kWaves>(a, q, e0, n, wave, &lo, &n_own);
+  const float scale = Td > 0.f ? kLog2eF / Td : kLog2eF;
+  float mx = -INFINITY;
+  int arg = 0x7FFFFFFF;
+  double S = 0.0;
+  if (n_own > 0) {
+    wave_row_stats<TD, kPieceBatch, kFirst>(x, n_own, scale, lane, &mx, &arg, &S, first);
+    arg += e0 + lo;
   }
+  // The two barriers order LDS accesses only (all LDS operations of this wavefront done, then meet): the fence of
+  // __syncthreads() would also wait for the record's store to be acknowledged, microseconds next to a saturating stream.
+  auto lds_barrier = []() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0), vmcnt and expcnt unconstrained
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  };
+  if (lane == 0) { s_mx[wave] = mx; s_arg[wave] = arg; s_S[wave] = S; }
+  lds_barrier();
+  if (tid == 0) {
+    float bm = -INFINITY;
+    int ba = 0x7FFFFFFF;
+    for (int w = 0; w < kWaves; ++w)
+      if (s_mx[w] > bm) { bm = s_mx[w]; ba = s_arg[w]; }     // ascending slices: a later equal maximum does not replace
+    double total = 0.0;
+    for (int w = 0; w < kWaves; ++w)
+      if (s_mx[w] != -INFINITY) total += s_S[w] * (double)__builtin_amdgcn_exp2f((s_mx[w] - bm) * scale);
+    DraftPiece r; r.mx = bm; r.arg = ba; r.sum = total;
+    *out = r;
+  }
+  lds_barrier();
+}
+
+// Statistics of draft row q from its pieces (ascending order, the merge rule of the slices above): lane-local.
+__device__ __forceinline__ void merge_draft_pieces(const StepArgs& a, int q, float Td, float* out_mx, double* out_S,
+                                                   int* out_arg) {
+  const int j0 = 0, j1 = a.plan.pieces(q) - 1;
+  const DraftPiece* rec = a.dpiece + (int64_t)q * kDraftPieces;
+  DraftPiece pc[kDraftPieces];
+#pragma unroll
+  for (int j = 0; j < kDraftPieces; ++j) pc[j] = rec[min(j, j1 - j0)];     // all loads before any use
+  const float scale = Td > 0.f ? kLog2eF / Td : kLog2eF;
+  float bm = -INFINITY;
+  int ba = 0x7FFFFFFF;
+#pragma unroll
+  for (int j = 0; j < kDraftPieces; ++j)
+    if (j <= j1 - j0 && pc[j].mx > bm) { bm = pc[j].mx; ba = pc[j].arg; }
+  double total = 0.0;
+#pragma unroll
+  for (int j = 0; j < kDraftPieces; ++j)
+    if (j <= j1 - j0 && pc[j].mx != -INFINITY) total += pc[j].sum * (double)__builtin_amdgcn_exp2f((pc[j].mx - bm) * scale);
+  *out_mx = bm; *out_S = total; *out_arg = ba;
 }
 
 }  // namespace otv

@@ -128,6 +128,40 @@ def test_softmax_statistics(dtype, V_t, V_d):
         np.testing.assert_allclose(ws["draft_row_sumexp"][q0:q1], wantq, rtol=2e-6)
 
 
+@pytest.mark.parametrize("ks,V_t,V_d", [([7, 3, 0, 9], 6000, 5003),      # 24 workgroups, 19 rows: 5 rows in two pieces
+                                        ([5, 5, 6], 12800, 4096),         # 50 workgroups, 16 rows: three pieces a row
+                                        ([5, 5, 6], 10240, 1111),         # 40 workgroups, 16 rows: 8 rows in three, 8 in two
+                                        ([8, 8], 4100, 1000),             # 17 workgroups, 16 rows: one row in two
+                                        ([30, 25, 1, 10], 1500, 24),      # 6 workgroups, 66 rows: whole rows in turn
+                                        ([40, 20], 2304, 40000)])         # long rows: more than one batch per wavefront
+def test_draft_row_statistics_from_lm_head_launch(ks, V_t, V_d):
+    """The LM-head launch that hosts the draft side shares the draft rows out over its multiplying workgroups, in pieces
+    of a row where there are more workgroups than rows; the launch that follows merges the pieces.  Row maximum and
+    argmax exact, sum of exponentials to 2e-6, for every way the rows can be shared out (bf16 rows, aligned or not)."""
+    ov, ot, Verifier, parity = _imports()
+    temps = [[1.0, 0.5, 0.0, 2.0][i % 4] for i in range(len(ks))]
+    dtemps = [[0.8, 1.0, 1.3, 0.0][i % 4] for i in range(len(ks))]
+    spec = CaseSpec(name=f"pieces_{len(ks)}_{V_t}_{V_d}", dtype="bf16", d=64, V_t=V_t, V_d=V_d, k=ks, temperature=temps,
+                    draft_temperature=dtemps, n_direct=min(V_d, V_t) // 2, data_seed=V_t + V_d, philox_seed=4)
+    case = make_case(spec)
+    assert case.M > 16                               # the wide kernel
+    v = Verifier.for_case(case, draft_side=ot.OT_DRAFT_SIDE_IN_LM_HEAD)
+    try:
+        inp = v.upload(case)
+        v.step(inp)
+        ws = v.workspace(case.M, case.K)
+    finally:
+        v.close()
+    Zq = ov.widen(case.draft_logits, "bf16")
+    assert np.array_equal(ws["draft_row_max"].astype(np.float64), Zq.max(axis=1))
+    assert np.array_equal(ws["draft_row_argmax"], Zq.argmax(axis=1))
+    for b in range(case.B):
+        q0, q1 = case.row_off[b] - b, case.row_off[b + 1] - b - 1
+        Td = float(case.draft_temperature[b]) or 1.0
+        wantq = np.exp((Zq[q0:q1] - Zq[q0:q1].max(axis=1, keepdims=True)) / Td).sum(axis=1)
+        np.testing.assert_allclose(ws["draft_row_sumexp"][q0:q1], wantq, rtol=2e-6)
+
+
 @pytest.mark.parametrize("M,d,V_t", [(20, 256, 1000), (60, 128, 2304), (96, 192, 777), (144, 256, 4100), (300, 136, 1111)])
 def test_row_statistics_from_lm_head_epilogue(M, d, V_t):
     """From 17 rows on the LM-head kernel emits the softmax partials itself (no second pass over the logits).
