@@ -66,16 +66,20 @@ typedef struct ot_ctx ot_ctx;                 /* owns the packed LM head, maps a
 typedef struct ot_ngram_cache ot_ngram_cache; /* owns the device hash table of one n-gram cache               */
 
 /* ---- ot_verify_init ----------------------------------------------------------------------------------- */
-/* The draft rows' softmax statistics and the translation (Eq. 1) need nothing from the LM head.  Where the bf16
- * LM-head kernel supports it (more than 16 rows, at most 255 sequences) they can run in extra workgroups of the
- * LM-head launch itself, which then also leaves the target rows' softmax partials, so that one launch follows it
- * instead of three.  That pays when the weight stream is long enough to hide them. */
+/* The draft rows' softmax statistics and what the drafted ids look up for the translation (Eq. 1: the drafted logit,
+ * the direct image, the n-gram cache probes) need nothing from the LM head.  Where the bf16 LM-head kernel supports it
+ * (more than 16 rows, at most 255 sequences) the LM-head launch itself can do that work: with up to 144 rows, where the
+ * launch is bound by the weight stream, every multiplying workgroup takes a piece of a draft row while its first loads
+ * are in flight; with more rows a few workgroups at the front of the launch take all of it.  The launch then also
+ * leaves the target rows' softmax partials, and one launch follows it (window walk, acceptance test, final draw)
+ * instead of three. */
 /* Capacity edges (all shapes inside max_batch / max_k are served; what changes is the launch structure):
  *   - more than 255 sequences in a step, 16 rows or fewer, OT_F32, or a step entered through
  *     ot_verify_step_from_logits: the draft side always runs as launches of its own after the LM head (two more
  *     launches, about 10 us at 16 sequences, about 25 us at 256 with a 32000-id draft vocabulary);
- *   - OT_DRAFT_SIDE_AUTO also chooses that structure when hosting would lengthen the LM-head launch, e.g. many
- *     sequences over a short weight stream.                                                                   */
+ *   - OT_DRAFT_SIDE_AUTO also chooses that structure when hosting would lengthen the LM-head launch: more than two
+ *     draft rows per multiplying workgroup (up to 144 rows), or front workgroups that would need more than half
+ *     of the launch (above).                                                                                     */
 #define OT_DRAFT_SIDE_AUTO        0   /* decide per step from its shape (estimate of both durations)               */
 #define OT_DRAFT_SIDE_IN_LM_HEAD  1   /* inside the LM-head launch whenever the kernel supports the shape          */
 #define OT_DRAFT_SIDE_SEPARATE    2   /* always as launches of their own after the LM head                         */

@@ -219,8 +219,8 @@ static int step_impl(ot_ctx* ctx, ot_ngram_cache* cache, const ot_step_in* in, c
   if (e == hipSuccess && !from_logits) {
     if (ctx->dtype == OT_BF16) {
       // Where its kernel supports it, the LM-head launch leaves per-tile softmax partials of the target rows (no second
-      // pass over the logits) and hosts the draft side of the step in extra workgroups: what follows it is then only
-      // the merge of those partials with the acceptance test, and the final draw.
+      // pass over the logits) and hosts the draft side of the step (the draft rows' statistics in pieces, the drafted
+      // ids' lookups): what follows it is then one launch that merges both, walks the windows, tests and draws.
       const bool supported = lmhead_bf16_draft_workers(M, ctx->Vp, in->B, K, ctx->n_cu) > 0 && K >= 1 && in->B <= kFusedMaxB;
       const bool host_it = supported && (ctx->draft_side == OT_DRAFT_SIDE_IN_LM_HEAD ||
                                          (ctx->draft_side == OT_DRAFT_SIDE_AUTO &&

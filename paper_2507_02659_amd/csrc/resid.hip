@@ -2,10 +2,13 @@
 // or free token from p), grid = (groups of 8 tiles of kResidTile target ids) x (sequences).
 //   final_draw_kernel   the outcome records of the acceptance test are in memory (written by the launch before).
 //   accept_draw_kernel  follows an LM-head launch that hosted the draft side: every workgroup first repeats the
-//                       acceptance test of its sequence (merge of the LM head's softmax partials, one wavefront per
-//                       target row, then one wavefront for the test: a few microseconds of work on data that sits in
-//                       L2, cheaper than a launch of its own), then takes part in the draw.  The workgroups of a
-//                       sequence reach the same outcome; only group 0 writes the test's outputs.
+//                       translation and the acceptance test of its sequence (one wavefront merges the pieces of the
+//                       draft rows' statistics and walks the window from the probe record while the others merge the
+//                       LM head's softmax partials, one wavefront per target row; then that wavefront runs the test:
+//                       a few microseconds of work on data that sits in L2, cheaper than a launch of its own), then
+//                       takes part in the draw.  The workgroups of a sequence reach the same outcome; only group 0
+//                       writes the outputs of the translation and the test, the draft rows' merged statistics and
+//                       the cache's use statistics.
 #include "accept.h"
 #include "resid.h"
 

@@ -1,14 +1,16 @@
 // Draft side of a verification step, as device functions shared by the kernels that host it: everything that needs
 // the drafter's logits and ids but nothing of the target's logits.
-//   * softmax statistics of the draft rows (Notation paragraph: q = softmax(zq / T_d)), one wavefront per row;
+//   * softmax statistics of the draft rows (Notation paragraph: q = softmax(zq / T_d)): one wavefront per row, or one
+//     workgroup per piece of a row with the pieces merged where they are used;
 //   * translation of the drafted window into the target vocabulary (Section "Cross-vocabulary N-gram Cache", Eq. 1):
 //     every window (start s, length L) of the drafted ids is probed in the n-gram table by its own thread; lane s of
 //     one wavefront prepares the segment that would start at s, and the window is then walked left to right as a chase
 //     through start + length: the longest cache hit at s yields one target token whose log q' is the sum of the L
 //     sub-token log-probabilities (the product of Eq. 1, kept in log space so that five or six factors of 1e-6 do not
 //     underflow), otherwise the direct image of d_s, and a draft id with neither ends the proposal.
-// The outcome of the walk is one LaneProposal per mapped position, held by lane j of the walking wavefront; it can be
-// parked in memory as a RowProposal for a later kernel (the acceptance test needs the target's logits).
+// The lookups of a sequence (drafted logits, direct images, table probes) need memory and can run early, next to the
+// LM head, which leaves them in a ProbeRecord; the walk itself is a few microseconds of one wavefront and runs where
+// the acceptance test does.  Its outcome is one LaneProposal per mapped position, held by lane j of that wavefront.
 #pragma once
 
 #include "device_math.h"
