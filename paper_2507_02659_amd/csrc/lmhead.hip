@@ -417,19 +417,21 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
     // barrier that followed its last slice (the weight ring may still receive the surplus refills; it is not used).
     // The statistics scratch (3 x 4 bytes per lane and row tile) reuses LDS of the main loop: either both hidden
     // buffers (maxima and sums in the first, columns in the second), or, where that holds fewer row tiles at once, one
-    // hidden buffer each for the maxima and the sums and the epilogue patch for the columns (not the weight ring: the
-    // surplus refills past the end of K still land there, and waiting for them costs a memory latency).  When even
-    // that is too small for all row tiles at once the row tiles are taken in groups of kStatMT.
+    // hidden buffer each for the maxima and the sums and the first weight-ring array for the columns (the ring is
+    // drained first: the surplus refills past the end of K still land there).  Not the epilogue patch: a wavefront that
+    // is done here goes on to turn its logits through its part of the patch while the merging threads still read.
+    // When even that is too small for all row tiles at once the row tiles are taken in groups of kStatMT.
     constexpr int kFitHidden = MT * KC / (16 * WPG), kFitSpread = MT * KC / (8 * WPG) < 4 * NW ? MT * KC / (8 * WPG) : 4 * NW;
     constexpr bool kSpread = (kFitSpread < MT ? kFitSpread : MT) > (kFitHidden < MT ? kFitHidden : MT);
     constexpr int kStatLim = kSpread ? (kFitSpread < MT ? kFitSpread : MT) : (kFitHidden < MT ? kFitHidden : MT);
     constexpr int kStatMT = MT % kStatLim == 0 ? kStatLim : (MT % (kStatLim - 1) == 0 ? kStatLim - 1 : 1);
     static_assert(kStatMT >= 1 && MT % kStatMT == 0, "row tiles split evenly into statistics groups");
     static_assert(sizeof(float) * WPG * kStatMT * 64 * (kSpread ? 1 : 2) <= sizeof(sA) &&
-                  sizeof(float) * WPG * kStatMT * 64 <= (kSpread ? sizeof(sPatch) : sizeof(sB)), "the scratch fits");
+                  sizeof(float) * WPG * kStatMT * 64 <= (kSpread ? sizeof(sW0) : sizeof(sB)), "the scratch fits");
     float* st_max = reinterpret_cast<float*>(sA);
     float* st_sum = kSpread ? reinterpret_cast<float*>(sB) : st_max + WPG * kStatMT * 64;
-    int32_t* st_arg = kSpread ? reinterpret_cast<int32_t*>(&sPatch[0][0]) : reinterpret_cast<int32_t*>(sB);
+    int32_t* st_arg = kSpread ? reinterpret_cast<int32_t*>(sW0) : reinterpret_cast<int32_t*>(sB);
+    if (kSpread) __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));   // before the barrier below
     for (int r = tid; r < MT * 16; r += WPG * 64) {
       const int row = min(row0 + r, M - 1);
       int lo = 0, hi = fs.B - 1;                    // sequence that owns the row: last b with row_off[b] <= row

@@ -26,21 +26,53 @@ __device__ inline int find_sequence(const int32_t* off, int B, int row, int shif
   return lo;
 }
 
+// The same for up to 256 sequences without a chain of dependent loads: every lane of the wavefront holds the first
+// row of sequences lane, lane + 64, ... (four independent loads, issued together), the predicate "starts at or before
+// `row`" is monotone in b, and the owner is the number of sequences it holds for, less one.  A workgroup's first loads
+// of logits then leave one round trip after its start, not five.
+constexpr int kBallotSequences = 256;
+struct SequenceStarts { int first_row[kBallotSequences / 64]; float temp[kBallotSequences / 64]; };
+__device__ inline SequenceStarts load_sequence_starts(const int32_t* off, const float* temperature, int B, int shift,
+                                                      int lane) {
+  SequenceStarts s;
+#pragma unroll
+  for (int j = 0; j < kBallotSequences / 64; ++j) {
+    const int b = min(64 * j + lane, B - 1);
+    s.first_row[j] = off[b] - shift * b;
+    s.temp[j] = temperature[b];
+  }
+  return s;
+}
+// temperature of the sequence that owns `row`
+__device__ inline float owner_temperature(const SequenceStarts& s, int B, int row, int lane) {
+  int owner = -1;
+#pragma unroll
+  for (int j = 0; j < kBallotSequences / 64; ++j)
+    owner += __popcll(__ballot(64 * j + lane < B && s.first_row[j] <= row));
+  float T = 1.f;
+#pragma unroll
+  for (int j = 0; j < kBallotSequences / 64; ++j) {
+    const float t = __shfl(s.temp[j], owner & 63);
+    if ((owner >> 6) == j) T = t;
+  }
+  return T;
+}
+
 template <typename T> struct Loader;
 template <> struct Loader<float> {
   static constexpr int kVec = 4;
-  __device__ static void load(const float* p, float* v) {
-    typedef float f32x4 __attribute__((ext_vector_type(4)));
-    const f32x4 x = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));   // a pass over rows far larger than L2
-    v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w;
+  typedef float Raw __attribute__((ext_vector_type(4)));
+  __device__ static Raw load(const float* p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const Raw*>(p));   // a pass over rows far larger than L2
   }
+  __device__ static void unpack(const Raw& x, float* v) { v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w; }
   __device__ static float one(const float* p) { return *p; }
 };
 template <> struct Loader<uint16_t> {
   static constexpr int kVec = 8;
-  __device__ static void load(const uint16_t* p, float* v) {
-    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    const u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  typedef uint32_t Raw __attribute__((ext_vector_type(4)));
+  __device__ static Raw load(const uint16_t* p) { return __builtin_nontemporal_load(reinterpret_cast<const Raw*>(p)); }
+  __device__ static void unpack(const Raw& x, float* v) {
     uint32_t w[4] = {x.x, x.y, x.z, x.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -51,10 +83,14 @@ template <> struct Loader<uint16_t> {
   __device__ static float one(const uint16_t* p) { return bf16_to_f32(*p); }
 };
 
-// Reduces chunk c of one row; thread 0 writes (max, sum, argmax) to the partial arrays.
-template <typename T, bool kAligned>
-__device__ inline void chunk_stats(const T* __restrict__ x_row, int V, int c, float scale, float* __restrict__ pmax,
-                                   double* __restrict__ psum, int32_t* __restrict__ parg, int64_t slot) {
+// Reduces chunk c of one row; thread 0 writes (max, sum, argmax) to the partial arrays.  All vector loads of the chunk
+// are issued before anything waits; scale_of() (the row's sequence and its temperature: it waits for loads issued before
+// the call, and issues one more) is called behind them, so that a workgroup's logits are on their way one instruction
+// after its start.
+template <typename T, bool kAligned, typename ScaleFn>
+__device__ __forceinline__ void chunk_stats(const T* __restrict__ x_row, int V, int c, ScaleFn scale_of,
+                                            float* __restrict__ pmax, double* __restrict__ psum,
+                                            int32_t* __restrict__ parg, int64_t slot) {
   constexpr int kVec = Loader<T>::kVec;
   constexpr int kLoads = kPerThread / kVec;
   const int tid = threadIdx.x;
@@ -65,12 +101,19 @@ __device__ inline void chunk_stats(const T* __restrict__ x_row, int V, int c, fl
   float v[kPerThread];
   float best = -INFINITY;
   int best_i = 0x7FFFFFFF;
+  typename Loader<T>::Raw raw[kLoads];
+#pragma unroll
+  for (int i = 0; i < kLoads; ++i) {
+    const int at = (i * kStatThreads + tid) * kVec;
+    if (kAligned && at + kVec <= n) raw[i] = Loader<T>::load(x + at);
+  }
+  const float scale = scale_of();
 #pragma unroll
   for (int i = 0; i < kLoads; ++i) {
     const int at = (i * kStatThreads + tid) * kVec;
     if (kAligned && at + kVec <= n) {
-      Loader<T>::load(x + at, &v[i * kVec]);
-    } else {
+      Loader<T>::unpack(raw[i], &v[i * kVec]);
+    } else {                                 // the ragged end of a row, or a row that is not 16-byte aligned
 #pragma unroll
       for (int e = 0; e < kVec; ++e) v[i * kVec + e] = (at + e < n) ? Loader<T>::one(x + at + e) : -INFINITY;
     }
@@ -123,21 +166,32 @@ __device__ inline void chunk_stats(const T* __restrict__ x_row, int V, int c, fl
 template <typename TD, bool kAlignedT, bool kAlignedD>
 __global__ __launch_bounds__(kStatThreads) void softmax_stats_kernel(StepArgs a) {
   const int n_target = a.M * a.ncht;                 // workgroups 0 .. n_target-1 take target chunks, the rest draft chunks
+  const int lane = threadIdx.x & 63;
+  const bool by_ballot = a.B <= kBallotSequences;
   if ((int)blockIdx.x < n_target) {
     const int row = blockIdx.x / a.ncht, c = blockIdx.x % a.ncht;
-    const int b = find_sequence(a.row_off, a.B, row, 0);
-    const float T_b = a.temperature[b];
-    const float scale = T_b > 0.f ? kLog2e / T_b : kLog2e;
-    chunk_stats<float, kAlignedT>(a.Z + (int64_t)row * a.ldz, a.V_t, c, scale, a.tpart_max, a.tpart_sum, a.tpart_arg,
+    SequenceStarts starts;
+    if (by_ballot) starts = load_sequence_starts(a.row_off, a.temperature, a.B, 0, lane);
+    auto scale_of = [&]() {
+      const float T_b = by_ballot ? owner_temperature(starts, a.B, row, lane)
+                                  : a.temperature[find_sequence(a.row_off, a.B, row, 0)];
+      return T_b > 0.f ? kLog2e / T_b : kLog2e;
+    };
+    chunk_stats<float, kAlignedT>(a.Z + (int64_t)row * a.ldz, a.V_t, c, scale_of, a.tpart_max, a.tpart_sum, a.tpart_arg,
                                   (int64_t)row * a.ncht + c);
   } else {
     const int id = blockIdx.x - n_target;
     const int drow = id / a.nchd, c = id % a.nchd;
-    const int b = find_sequence(a.row_off, a.B, drow, 1);
-    const float T_b = a.draft_temperature ? a.draft_temperature[b] : a.temperature[b];
-    const float scale = T_b > 0.f ? kLog2e / T_b : kLog2e;
+    SequenceStarts starts;
+    const float* temps = a.draft_temperature ? a.draft_temperature : a.temperature;
+    if (by_ballot) starts = load_sequence_starts(a.row_off, temps, a.B, 1, lane);
+    auto scale_of = [&]() {
+      const float T_b = by_ballot ? owner_temperature(starts, a.B, drow, lane)
+                                  : temps[find_sequence(a.row_off, a.B, drow, 1)];
+      return T_b > 0.f ? kLog2e / T_b : kLog2e;
+    };
     const TD* x = static_cast<const TD*>(a.draft_logits) + (int64_t)drow * a.V_d;
-    chunk_stats<TD, kAlignedD>(x, a.V_d, c, scale, a.dpart_max, a.dpart_sum, a.dpart_arg, (int64_t)drow * a.nchd + c);
+    chunk_stats<TD, kAlignedD>(x, a.V_d, c, scale_of, a.dpart_max, a.dpart_sum, a.dpart_arg, (int64_t)drow * a.nchd + c);
   }
 }
 
