@@ -49,6 +49,27 @@ __device__ inline void merge_partials(const float* __restrict__ pmax, const doub
   }
 }
 
+// Lanes of a wavefront hold running statistics r of parts of one row (exponent scale sc): merges them by shuffles in a
+// fixed order; lane 0 publishes the row's (max, sum, argmax) to LDS slot `at` and, if asked, to the workspace.
+__device__ inline void wave_publish_row(const RunStat& r, float sc, int row, int lane, float* s_mx, double* s_S,
+                                        int* s_arg, int at, bool to_workspace, float* g_mx, double* g_S, int32_t* g_arg) {
+  float mx = r.mx;
+  int arg = r.arg;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const float om = __shfl_xor(mx, off);
+    const int oa = __shfl_xor(arg, off);
+    if (om > mx || (om == mx && oa < arg)) { mx = om; arg = oa; }
+  }
+  double S = r.mx == -INFINITY ? 0.0 : r.sum * (double)__builtin_amdgcn_exp2f((r.mx - mx) * sc);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) S += __shfl_xor(S, off);
+  if (lane == 0) {
+    s_mx[at] = mx; s_S[at] = S; s_arg[at] = arg;
+    if (to_workspace) { g_mx[row] = mx; g_S[row] = S; g_arg[row] = arg; }
+  }
+}
+
 // Merges the LM head's partials of one target row (nfine of them, one per column tile): called by a whole wavefront.
 // A lane requests eight 16-byte partials at a time before it looks at any of them (one round trip to memory for up
 // to 512 tiles) and keeps a running maximum with the sum rescaled to it; the lanes are then merged by shuffles.  Sums
@@ -88,21 +109,47 @@ __device__ inline void merge_fused_row(const Partial* __restrict__ part, int nfi
       }
     }
   }
-  float mx = r.mx;
-  int arg = r.arg;
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) {
-    const float om = __shfl_xor(mx, off);
-    const int oa = __shfl_xor(arg, off);
-    if (om > mx || (om == mx && oa < arg)) { mx = om; arg = oa; }
+  wave_publish_row(r, sc, row, lane, s_mx, s_S, s_arg, at, to_workspace, g_mx, g_S, g_arg);
+}
+
+// The same for the chunk partials of the statistics launch (three arrays, nch entries per row): lane c takes chunks
+// c, c + 64, ...
+__device__ inline void merge_chunk_row(const float* __restrict__ pmax, const double* __restrict__ psum,
+                                       const int32_t* __restrict__ parg, int nch, int row, double invT, int lane,
+                                       float* s_mx, double* s_S, int* s_arg, int at, bool to_workspace, float* g_mx,
+                                       double* g_S, int32_t* g_arg) {
+  const int64_t o = (int64_t)row * nch;
+  const float sc = (float)invT * kLog2eF;
+  RunStat r;
+  for (int c = lane; c < nch; c += 64) {
+    const float m = pmax[o + c];
+    const int ai = parg[o + c];
+    const double sum = psum[o + c];
+    if (m > r.mx || (m == r.mx && ai < r.arg)) {
+      r.sum *= (double)__builtin_amdgcn_exp2f((r.mx - m) * sc);        // r.mx = -inf: the sum is 0 and stays 0
+      r.mx = m; r.arg = ai;
+    }
+    if (m != -INFINITY) r.sum += sum * (double)__builtin_amdgcn_exp2f((m - r.mx) * sc);
   }
-  double S = r.mx == -INFINITY ? 0.0 : r.sum * (double)__builtin_amdgcn_exp2f((r.mx - mx) * sc);
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) S += __shfl_xor(S, off);
-  if (lane == 0) {
-    s_mx[at] = mx; s_S[at] = S; s_arg[at] = arg;
-    if (to_workspace) { g_mx[row] = mx; g_S[row] = S; g_arg[row] = arg; }
+  wave_publish_row(r, sc, row, lane, s_mx, s_S, s_arg, at, to_workspace, g_mx, g_S, g_arg);
+}
+
+// Statistics of draft row q from the chunk partials of the statistics launch (ascending chunks): lane-local.
+__device__ inline void merge_draft_chunks(const StepArgs& a, int q, float Td, float* out_mx, double* out_S, int* out_arg) {
+  const int64_t o = (int64_t)q * a.nchd;
+  const float sc = Td > 0.f ? kLog2eF / Td : kLog2eF;
+  float bm = -INFINITY;
+  int ba = 0x7FFFFFFF;
+  for (int c = 0; c < a.nchd; ++c) {
+    const float m = a.dpart_max[o + c];
+    if (m > bm) { bm = m; ba = a.dpart_arg[o + c]; }       // ascending chunks: a later equal maximum does not replace
   }
+  double total = 0.0;
+  for (int c = 0; c < a.nchd; ++c) {
+    const float m = a.dpart_max[o + c];
+    if (m != -INFINITY) total += a.dpart_sum[o + c] * (double)__builtin_amdgcn_exp2f((m - bm) * sc);
+  }
+  *out_mx = bm; *out_S = total; *out_arg = ba;
 }
 
 // The acceptance test of sequence b by one wavefront (lane = mapped position).  P is the lane's proposal (P.m, P.flags

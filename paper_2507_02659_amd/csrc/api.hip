@@ -239,9 +239,12 @@ static int step_impl(ot_ctx* ctx, ot_ngram_cache* cache, const ot_step_in* in, c
       e = launch_lmhead_f32(static_cast<const float*>(in->hidden), M, ctx->d, ctx->Wf, ctx->Z, ctx->V_t, a.ldz, st);
   }
   OT_MARK(1);
+  // Without the LM head's help the statistics get a launch of their own; with at most kFusedMaxB sequences it also does
+  // the lookups, and one launch follows it as above; with more, the translation and the test get a launch of their own.
+  if (!a.hosted && in->B <= kFusedMaxB) a.chunked = 1;
   if (e == hipSuccess && !a.hosted) e = launch_softmax_stats(a, st);
   OT_MARK(2);
-  if (e == hipSuccess && !a.hosted) e = launch_translate_accept(a, st);
+  if (e == hipSuccess && !a.hosted && !a.chunked) e = launch_translate_accept(a, st);
   OT_MARK(3);
   if (e == hipSuccess) e = launch_final_draw(a, in->row_off_host, st);
   OT_MARK(4);

@@ -156,8 +156,10 @@ struct StepArgs {
   DraftPiece* dpiece;    // [K, kDraftPieces] statistics of the pieces of the draft rows, left by the LM-head launch
   PiecePlan plan;        // how the LM-head launch shared out the draft rows
   ProbeRecord* probe;    // [B] what the drafted ids of each sequence look up (see ProbeRecord), left by the LM-head launch
-  int32_t hosted;        // the LM-head launch left the target rows' softmax partials (`fused`) and the draft rows'
-                         // statistics (drow_*): one launch follows it, which translates, tests and draws
+  int32_t hosted;        // the LM-head launch left the target rows' softmax partials (`fused`), the draft rows' pieces
+                         // and the probe records: one launch follows it, which translates, tests and draws
+  int32_t chunked;       // the statistics launch left chunk partials (tpart_*, dpart_*) and the probe records: the same
+                         // one launch follows it (at most kFusedMaxB sequences)
   FinalInfo* fin;        // [B]
   int32_t ntiles;        // residual tiles per row
   double* tile_r; double* tile_p;                            // [B, ntiles]

@@ -34,7 +34,9 @@ constexpr int64_t kRepeatedMergeBytes = 32 << 20;
 
 // kDraw = false: grid = (1) x (sequences); the workgroup only runs the test and leaves the outcome record in memory for
 // a final_draw_kernel launch (used when repeating the test in every tile group would cost more than a launch).
-template <bool kDraw>
+// kChunks: the partials come from the statistics launch (chunk partials in three arrays per side) instead of the
+// LM head's epilogue and draft-row pieces.
+template <bool kDraw, bool kChunks>
 __global__ __launch_bounds__(kDrawThreads) void accept_draw_kernel(StepArgs a, RowOffsets ro) {
   const int b = blockIdx.y, grp = blockIdx.x, tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
@@ -73,7 +75,8 @@ __global__ __launch_bounds__(kDrawThreads) void accept_draw_kernel(StepArgs a, R
     s_d.hit[lane] = rec->hit[lane]; s_d.zq[lane] = rec->zq[lane]; s_d.dm[lane] = rec->dm[lane];
     if (lane < k) {
       float mxq; double Sq; int argq;
-      merge_draft_pieces(a, q0 + lane, Td, &mxq, &Sq, &argq);
+      if (kChunks) merge_draft_chunks(a, q0 + lane, Td, &mxq, &Sq, &argq);
+      else merge_draft_pieces(a, q0 + lane, Td, &mxq, &Sq, &argq);
       s_d.qmx[lane] = mxq; s_d.qS[lane] = Sq; s_d.qarg[lane] = argq;
       if (lead) { a.drow_max[q0 + lane] = mxq; a.drow_sum[q0 + lane] = Sq; a.drow_arg[q0 + lane] = argq; }
     }
@@ -89,9 +92,14 @@ __global__ __launch_bounds__(kDrawThreads) void accept_draw_kernel(StepArgs a, R
     }
     if (!(P.flags & OT_FLAG_BAD_ID) && lane < P.m && T > 0.f) z_tok = a.Z[(int64_t)(r0 + lane) * a.ldz + P.t];
   }
-  for (int row = wave; row <= k; row += kDrawWaves)
-    merge_fused_row(a.fused.part, a.fused.nfine, r0 + row, invT, lane, s_pmx, s_pS, s_parg, row, lead, a.row_max, a.row_sum,
-                    a.row_arg);
+  for (int row = wave; row <= k; row += kDrawWaves) {
+    if (kChunks)
+      merge_chunk_row(a.tpart_max, a.tpart_sum, a.tpart_arg, a.ncht, r0 + row, invT, lane, s_pmx, s_pS, s_parg, row, lead,
+                      a.row_max, a.row_sum, a.row_arg);
+    else
+      merge_fused_row(a.fused.part, a.fused.nfine, r0 + row, invT, lane, s_pmx, s_pS, s_parg, row, lead, a.row_max,
+                      a.row_sum, a.row_arg);
+  }
   // The inverse map of this wavefront's ids is needed last (by the tile masses) and asked for here, behind the loads
   // that the test waits for: loads return in issue order, and asked for first it held those back by its own latency.
   if (kDraw) load_tmap<kPerLane>(a.tmap, a.V_t, draw_first_id(grp, wave, lane), 64, dv);
@@ -112,12 +120,20 @@ __global__ __launch_bounds__(kDrawThreads) void accept_draw_kernel(StepArgs a, R
 
 }  // namespace
 
-// hosted: the LM-head launch left its softmax partials and the draft rows' statistics (then B <= kFusedMaxB and
-// row_off_host holds the B + 1 row offsets); otherwise a.fin is filled.
+// hosted: the LM-head launch left its softmax partials, the draft rows' pieces and the probe records; chunked: the
+// statistics launch left its chunk partials and the probe records (in both cases B <= kFusedMaxB and row_off_host holds
+// the B + 1 row offsets); otherwise a.fin is filled.
 hipError_t launch_final_draw(const StepArgs& a, const int32_t* row_off_host, hipStream_t stream) {
   if (a.B == 0) return hipSuccess;
   const dim3 grid(ceil_div(a.ntiles, kGroupTiles), a.B), block(kDrawThreads);
   const size_t lds = 2 * (size_t)a.ntiles * sizeof(double);
+  if (a.chunked) {
+    if (a.B > kFusedMaxB || a.hosted) return hipErrorInvalidValue;
+    RowOffsets ro;
+    for (int b = 0; b <= kFusedMaxB; ++b) ro.v[b] = row_off_host[b <= a.B ? b : a.B];
+    hipLaunchKernelGGL((accept_draw_kernel<true, true>), grid, block, lds, stream, a, ro);   // a few chunks per row: always one launch
+    return hipGetLastError();
+  }
   if (a.hosted) {
     if (a.B > kFusedMaxB) return hipErrorInvalidValue;
     RowOffsets ro;
@@ -126,10 +142,10 @@ hipError_t launch_final_draw(const StepArgs& a, const int32_t* row_off_host, hip
     // about the traffic that costs as much as a launch this is one launch; beyond it the test gets a launch of its own.
     const int64_t repeated = (int64_t)a.M * a.fused.nfine * (int64_t)sizeof(Partial) * grid.x;
     if (repeated <= kRepeatedMergeBytes) {
-      hipLaunchKernelGGL(accept_draw_kernel<true>, grid, block, lds, stream, a, ro);
+      hipLaunchKernelGGL((accept_draw_kernel<true, false>), grid, block, lds, stream, a, ro);
       return hipGetLastError();
     }
-    hipLaunchKernelGGL(accept_draw_kernel<false>, dim3(1, a.B), block, 0, stream, a, ro);
+    hipLaunchKernelGGL((accept_draw_kernel<false, false>), dim3(1, a.B), block, 0, stream, a, ro);
   }
   hipLaunchKernelGGL(final_draw_kernel, grid, block, lds, stream, a);
   return hipGetLastError();

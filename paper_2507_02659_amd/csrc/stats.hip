@@ -6,9 +6,12 @@
 // dtype): one workgroup reduces one chunk of kStatChunk logits of one row.  The chunk is read once into registers
 // (16-byte loads, consecutive lanes on consecutive vectors), reduced to its maximum through wavefront shuffles and
 // LDS, and only then exponentiated, so every logit is read from HBM exactly once.  The per-chunk partials are
-// merged in a fixed order by the consumer (the translate-and-accept kernel).
+// merged in a fixed order by the consumer.  With a.chunked the launch also carries one workgroup per sequence that
+// looks up what its drafted ids need (drafted logit, direct image, n-gram table probes: Eq. 1) and leaves a
+// ProbeRecord, so that a single launch can follow (walk, acceptance test, final draw).
 #include "device_math.h"
 #include "otv_internal.h"
+#include "translate.h"
 
 namespace otv {
 namespace {
@@ -168,6 +171,19 @@ __global__ __launch_bounds__(kStatThreads) void softmax_stats_kernel(StepArgs a)
   const int n_target = a.M * a.ncht;                 // workgroups 0 .. n_target-1 take target chunks, the rest draft chunks
   const int lane = threadIdx.x & 63;
   const bool by_ballot = a.B <= kBallotSequences;
+  if ((int)blockIdx.x >= n_target + a.K * a.nchd) {  // only with a.chunked: the lookups of one sequence
+    __shared__ DraftLds s_d;
+    const int b = blockIdx.x - (n_target + a.K * a.nchd), tid = threadIdx.x;
+    const int r0 = a.row_off[b], k = a.row_off[b + 1] - r0 - 1;
+    draft_lds_reset(&s_d, tid);
+    __syncthreads();
+    fetch_ids_and_probe(a, r0 - b, k, tid, kStatThreads, &s_d);
+    __syncthreads();
+    ProbeRecord* rec = a.probe + b;
+    if (tid < 64) { rec->hit[tid] = s_d.hit[tid]; rec->zq[tid] = s_d.zq[tid]; rec->dm[tid] = s_d.dm[tid]; }
+    if (tid == 0) rec->bad = s_d.bad;
+    return;
+  }
   if ((int)blockIdx.x < n_target) {
     const int row = blockIdx.x / a.ncht, c = blockIdx.x % a.ncht;
     SequenceStarts starts;
@@ -197,7 +213,7 @@ __global__ __launch_bounds__(kStatThreads) void softmax_stats_kernel(StepArgs a)
 
 template <typename TD>
 hipError_t launch_typed(const StepArgs& a, bool at, bool ad, hipStream_t stream) {
-  dim3 grid(a.M * a.ncht + a.K * a.nchd), block(kStatThreads);
+  dim3 grid(a.M * a.ncht + a.K * a.nchd + (a.chunked ? a.B : 0)), block(kStatThreads);
   if (at && ad) hipLaunchKernelGGL((softmax_stats_kernel<TD, true, true>), grid, block, 0, stream, a);
   else if (at) hipLaunchKernelGGL((softmax_stats_kernel<TD, true, false>), grid, block, 0, stream, a);
   else if (ad) hipLaunchKernelGGL((softmax_stats_kernel<TD, false, true>), grid, block, 0, stream, a);
@@ -208,7 +224,7 @@ hipError_t launch_typed(const StepArgs& a, bool at, bool ad, hipStream_t stream)
 }  // namespace
 
 hipError_t launch_softmax_stats(const StepArgs& a, hipStream_t stream) {
-  if (a.M + a.K == 0) return hipSuccess;
+  if (a.M + a.K + (a.chunked ? a.B : 0) == 0) return hipSuccess;
   const bool at = (a.ldz % 4) == 0 && (reinterpret_cast<uintptr_t>(a.Z) % 16) == 0;
   const bool base16 = (reinterpret_cast<uintptr_t>(a.draft_logits) % 16) == 0;
   if (a.dtype == OT_BF16) return launch_typed<uint16_t>(a, at, base16 && a.V_d % 8 == 0, stream);
