@@ -74,10 +74,12 @@ typedef struct ot_ngram_cache ot_ngram_cache; /* owns the device hash table of o
  * leaves the target rows' softmax partials, and one launch follows it (window walk, acceptance test, final draw)
  * instead of three. */
 /* Capacity edges (all shapes inside max_batch / max_k are served; what changes is the launch structure):
- *   - more than 255 sequences in a step, 16 rows or fewer, OT_F32, or a step entered through
- *     ot_verify_step_from_logits: the draft side always runs as launches of its own after the LM head (two more
- *     launches, about 10 us at 16 sequences, about 25 us at 256 with a 32000-id draft vocabulary);
- *   - OT_DRAFT_SIDE_AUTO also chooses that structure when hosting would lengthen the LM-head launch: more than two
+ *   - 16 rows or fewer, OT_F32, or a step entered through ot_verify_step_from_logits: the draft side always runs
+ *     after the LM head (the softmax statistics of all rows and the lookups as a launch of their own, then the launch
+ *     that walks, tests and draws: one launch more, a few microseconds);
+ *   - more than 255 sequences in a step: the same, and the translation with the acceptance test gets a launch of its
+ *     own as well (two launches more, about 25 us at 256 sequences with a 32000-id draft vocabulary);
+ *   - OT_DRAFT_SIDE_AUTO also chooses the first of these when hosting would lengthen the LM-head launch: more than two
  *     draft rows per multiplying workgroup (up to 144 rows), or front workgroups that would need more than half
  *     of the launch (above).                                                                                     */
 #define OT_DRAFT_SIDE_AUTO        0   /* decide per step from its shape (estimate of both durations)               */
