@@ -168,12 +168,17 @@ __device__ __forceinline__ void chunk_stats(const T* __restrict__ x_row, int V, 
 // Rows 0..M-1 are target rows, rows M..M+K-1 draft rows.  TD is the draft logits' storage type.
 template <typename TD, bool kAlignedT, bool kAlignedD>
 __global__ __launch_bounds__(kStatThreads) void softmax_stats_kernel(StepArgs a) {
-  const int n_target = a.M * a.ncht;                 // workgroups 0 .. n_target-1 take target chunks, the rest draft chunks
+  // With a.chunked the first B workgroups look up one sequence's drafted ids each: chains of dependent loads, started
+  // first so that they run underneath the stream of the others.  Then n_target workgroups take target chunks, the rest
+  // draft chunks.
+  const int n_lookup = a.chunked ? a.B : 0;
+  const int wg = (int)blockIdx.x - n_lookup;
+  const int n_target = a.M * a.ncht;
   const int lane = threadIdx.x & 63;
   const bool by_ballot = a.B <= kBallotSequences;
-  if ((int)blockIdx.x >= n_target + a.K * a.nchd) {  // only with a.chunked: the lookups of one sequence
+  if (wg < 0) {
     __shared__ DraftLds s_d;
-    const int b = blockIdx.x - (n_target + a.K * a.nchd), tid = threadIdx.x;
+    const int b = blockIdx.x, tid = threadIdx.x;
     const int r0 = a.row_off[b], k = a.row_off[b + 1] - r0 - 1;
     draft_lds_reset(&s_d, tid);
     __syncthreads();
@@ -184,8 +189,8 @@ __global__ __launch_bounds__(kStatThreads) void softmax_stats_kernel(StepArgs a)
     if (tid == 0) rec->bad = s_d.bad;
     return;
   }
-  if ((int)blockIdx.x < n_target) {
-    const int row = blockIdx.x / a.ncht, c = blockIdx.x % a.ncht;
+  if (wg < n_target) {
+    const int row = wg / a.ncht, c = wg % a.ncht;
     SequenceStarts starts;
     if (by_ballot) starts = load_sequence_starts(a.row_off, a.temperature, a.B, 0, lane);
     auto scale_of = [&]() {
@@ -196,7 +201,7 @@ __global__ __launch_bounds__(kStatThreads) void softmax_stats_kernel(StepArgs a)
     chunk_stats<float, kAlignedT>(a.Z + (int64_t)row * a.ldz, a.V_t, c, scale_of, a.tpart_max, a.tpart_sum, a.tpart_arg,
                                   (int64_t)row * a.ncht + c);
   } else {
-    const int id = blockIdx.x - n_target;
+    const int id = wg - n_target;
     const int drow = id / a.nchd, c = id % a.nchd;
     SequenceStarts starts;
     const float* temps = a.draft_temperature ? a.draft_temperature : a.temperature;
