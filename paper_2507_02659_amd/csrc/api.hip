@@ -224,7 +224,7 @@ static int step_impl(ot_ctx* ctx, ot_ngram_cache* cache, const ot_step_in* in, c
       const bool supported = lmhead_bf16_draft_workers(M, ctx->Vp, in->B, K, ctx->n_cu) > 0 && K >= 1 && in->B <= kFusedMaxB;
       const bool host_it = supported && (ctx->draft_side == OT_DRAFT_SIDE_IN_LM_HEAD ||
                                          (ctx->draft_side == OT_DRAFT_SIDE_AUTO &&
-                                          lmhead_bf16_hosts_draft_side(M, ctx->d, ctx->Vp, in->B, K, ctx->n_cu)));
+                                          lmhead_bf16_hosts_draft_side(M, ctx->d, ctx->Vp, in->B, K, ctx->V_d, ctx->n_cu)));
       const int nfine = host_it ? lmhead_bf16_fused_partials(M, ctx->Vp, ctx->n_cu) : 0;
       if (nfine > 0) {
         a.fused.row_off = in->row_off; a.fused.temperature = in->temperature; a.fused.B = in->B; a.fused.nfine = nfine;

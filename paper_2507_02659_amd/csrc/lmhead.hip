@@ -100,6 +100,8 @@ __device__ inline void lds_barrier() {
 }
 
 constexpr int gcd_c(int a, int b) { return b == 0 ? a : gcd_c(b, a % b); }
+// largest divisor of n that is at most `limit` (limit >= 1)
+constexpr int largest_divisor_c(int n, int limit) { return n % limit == 0 ? limit : largest_divisor_c(n, limit - 1); }
 
 template <int MT, int PF, int WPG, int KC, int NW, bool W_ONCE>
 __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16_t* __restrict__ H, int M, int d,
@@ -219,6 +221,42 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
       first = false;
     }
   };
+  // The same for one wavefront on its own (front workgroups: every wavefront is a worker of the plan): no workgroup
+  // barriers, and 16 sixteen-byte loads in flight per lane, because a workgroup that only reads next to the other
+  // workgroups' streams gets the bytes it keeps in flight once per several microseconds.
+  auto wave_piece_jobs = [&](int job) {
+    const float* temps = ds.draft_temperature ? ds.draft_temperature : fs.temperature;
+#pragma unroll
+    for (int j = 0; j < kSeqRegs; ++j) {
+      const int b = min(64 * j + lane, fs.B - 1);
+      seq_before[j] = fs.row_off[b] - b;
+      seq_temp[j] = temps[b];
+    }
+    int q, i, e0, n;
+    ds.plan.locate(job, &q, &i);
+    for (; q < ds.K; q += ds.plan.workers) {
+      PiecePlan::span(ds.V_d, ds.plan.pieces(q), i, &e0, &n);
+      int owner = -1;
+      float Td = 1.f;
+#pragma unroll
+      for (int j = 0; j < kSeqRegs; ++j) {
+        const bool before = 64 * j + lane < fs.B && seq_before[j] <= q;
+        owner += __popcll(__ballot(before));
+      }
+#pragma unroll
+      for (int j = 0; j < kSeqRegs; ++j) {
+        const float t = __shfl(seq_temp[j], owner & 63);
+        if ((owner >> 6) == j) Td = t;
+      }
+      DraftPiece r; r.mx = -INFINITY; r.arg = 0x7FFFFFFF; r.sum = 0.0;
+      if (n > 0) {
+        wave_row_stats<uint16_t, 16>(static_cast<const uint16_t*>(ds.draft_logits) + (int64_t)q * ds.V_d + e0, n,
+                                     Td > 0.f ? kLog2eF / Td : kLog2eF, lane, &r.mx, &r.arg, &r.sum);
+        r.arg += e0;
+      }
+      if (lane == 0) ds.dpiece[(int64_t)q * kDraftPieces + i] = r;
+    }
+  };
   auto lookup_job = [&](int b) {               // the sequences are staged in LDS
     DraftLds* probe_lds = reinterpret_cast<DraftLds*>(&sPatch[0][0]);
     static_assert(sizeof(DraftLds) <= sizeof(sPatch), "the lookups' scratch fits into the epilogue patch");
@@ -262,10 +300,13 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
   if (wg < 0) {
     // Front workgroups: the whole draft side of a launch that is bound by the matrix cores (several M-blocks), where a
     // piece in front of every multiplying workgroup's loop would add its time to each of them.  They start first and
-    // are done long before the launch ends; front workgroup h takes rows h, h + n_front, ... and its share of lookups.
+    // are done long before the launch ends; every wavefront of them is a worker of the plan, and front workgroup h takes
+    // its share of the lookups.
+    // The lookups come first: their chains of dependent loads are short while the launch has not yet filled the
+    // memory system, and several times as long afterwards.
     const int h = (int)blockIdx.x;
-    if (h < n_piece_jobs) { piece_request(h); piece_job(h); }
     helper_lookups(h, n_front);
+    if (h * WPG + wave < n_piece_jobs) wave_piece_jobs(h * WPG + wave);
     return;
   }
   if (col_tile >= n_col_tiles) {
@@ -288,12 +329,6 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
   const int row0 = m_block * (MT * 16);
   // fragment (16-column tile t, step ks) sits at 16-byte unit (t/4) * packed_tile_units(nks) + (ks * 4 + t%4) * 64 + lane
   const uint4* wp = Wp + (int64_t)(t16 / 4) * packed_tile_units(nks) + (t16 % 4) * 64 + lane;
-
-  f32x4 acc[MT][NW];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int nw = 0; nw < NW; ++nw) acc[mt][nw] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   // Swizzle key of a row: the 16-byte chunks of a row are XORed with the low bits of the row index (measured: with
   // 128-byte rows, folding bit 3 of the row into the key as well stalls 46 % of the LDS cycles on bank conflicts,
@@ -339,7 +374,9 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
   // This workgroup's piece of the draft rows is asked for first: it is reduced while the first weight fragments and the
   // hidden slice, asked for right behind it, land.  2 to 3 us that the launch which follows no longer has to wait for.
   const int own_job = col_tile * m_blocks + m_block;
-  const bool has_job = n_front == 0 && own_job < n_piece_jobs;
+  // (only a launch with a single M-block gives its multiplying workgroups pieces: W_ONCE says so at compile time, which
+  // keeps the piece's registers out of the kernels whose accumulators leave none to spare)
+  const bool has_job = W_ONCE && n_front == 0 && own_job < n_piece_jobs;
   if (has_job) piece_request(own_job);
   request(0, sA);
 #pragma unroll
@@ -351,6 +388,12 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
   // Without idle workgroups to take them, the lookups go to the multiplying workgroups as well, from the last one down.
   if (hosts && !helpers_look_up && n_front == 0)
     for (int b = n_col_tiles * m_blocks - 1 - own_job; b < fs.B; b += n_col_tiles * m_blocks) lookup_job(b);
+
+  f32x4 acc[MT][NW];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int nw = 0; nw < NW; ++nw) acc[mt][nw] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   const int a_row = lane & 15, a_grp = lane >> 4;
   // one slice out of buffer hs; kc = its first step, s0 = ring array of that step (compile-time after unrolling)
@@ -422,9 +465,11 @@ __global__ __launch_bounds__(WPG * 64) void lmhead_bf16_wide_kernel(const uint16
     // is done here goes on to turn its logits through its part of the patch while the merging threads still read.
     // When even that is too small for all row tiles at once the row tiles are taken in groups of kStatMT.
     constexpr int kFitHidden = MT * KC / (16 * WPG), kFitSpread = MT * KC / (8 * WPG) < 4 * NW ? MT * KC / (8 * WPG) : 4 * NW;
-    constexpr bool kSpread = (kFitSpread < MT ? kFitSpread : MT) > (kFitHidden < MT ? kFitHidden : MT);
-    constexpr int kStatLim = kSpread ? (kFitSpread < MT ? kFitSpread : MT) : (kFitHidden < MT ? kFitHidden : MT);
-    constexpr int kStatMT = MT % kStatLim == 0 ? kStatLim : (MT % (kStatLim - 1) == 0 ? kStatLim - 1 : 1);
+    // row tiles per group: the largest divisor of MT that fits, in whichever layout allows the larger one
+    constexpr int kGroupHidden = largest_divisor_c(MT, kFitHidden < MT ? kFitHidden : MT);
+    constexpr int kGroupSpread = largest_divisor_c(MT, kFitSpread < MT ? kFitSpread : MT);
+    constexpr bool kSpread = kGroupSpread > kGroupHidden;
+    constexpr int kStatMT = kSpread ? kGroupSpread : kGroupHidden;
     static_assert(kStatMT >= 1 && MT % kStatMT == 0, "row tiles split evenly into statistics groups");
     static_assert(sizeof(float) * WPG * kStatMT * 64 * (kSpread ? 1 : 2) <= sizeof(sA) &&
                   sizeof(float) * WPG * kStatMT * 64 <= (kSpread ? sizeof(sW0) : sizeof(sB)), "the scratch fits");
@@ -644,17 +689,39 @@ constexpr int kSingleBlockRows = 144;
 // Rough duration of an LM-head launch: the weights stream at 6 TB/s or the product runs at 1 PFLOP/s, whichever is longer.
 double lmhead_launch_us(int M, int d, int Vp) { return std::max(2.0 * d * (double)Vp / 6.0e6, 2.0 * M * d * (double)Vp / 1.0e9); }
 
-// Front workgroups of a launch that hosts the draft side with several M-blocks: one per sequence or per 16 draft rows,
-// whichever is more; a multiple of 8 (the XCD mapping of the multiplying workgroups holds), 8 to 64.  0: one M-block,
-// where the multiplying workgroups take the draft side themselves.
-int lmhead_bf16_front_workgroups(int M, int B, int K) {
-  if (M <= kSingleBlockRows) return 0;
-  return std::min(64, std::max(8, ceil_div(std::max(B, ceil_div(K, 16)), 8) * 8));
+// Row tiles per M-block when more than 144 rows run as several M-blocks per column tile (their weight streams meet in
+// one L2).  That regime is bound by the L2 -> LDS traffic and by LDS reads, and the time of an M-block was measured to
+// grow almost in proportion to its height (about 1.3 row tiles of fixed cost per block: 144, 256, 288 rows take 150,
+// 251, 284 us at d = 4096, V_t = 128256), so the height that minimises blocks x (1.3 + row tiles) is taken: mostly the
+// one that pads least.
+int tall_block_tiles(int M) {
+  int best_mt = 9;
+  int best_cost = ceil_div(M, 144) * (13 + 10 * 9);
+  for (int mt : {10, 12, 14, 16, 18}) {
+    const int cost = ceil_div(M, 16 * mt) * (13 + 10 * mt);
+    if (cost <= best_cost) { best_cost = cost; best_mt = mt; }
+  }
+  return best_mt;
 }
+
+// Front workgroups of a launch that hosts the draft side with several M-blocks: one per four sequences (the lookups go
+// four sequences at a time), a multiple of 8 (the XCD mapping of the multiplying workgroups holds), 8 to 64.  A
+// workgroup that only reads, next to the multiplying ones, draws 5 to 10 GB/s however much it keeps in flight (measured:
+// 8 of them need about 230 us for the 9.2 MB of 144 draft rows, 64 of them 35 us for 23 MB), so the compute-unit time
+// the draft rows cost is given by their bytes; few front workgroups keep that time inside the slack of the last round
+// of multiplying workgroups, many push some of those into a round of their own (160 rows, 501 multiplying workgroups in
+// two rounds on 256 CUs: 64 front workgroups 257 us per step, separate launches 243).  0: one M-block, where the
+// multiplying workgroups take the draft side themselves.
+constexpr double kFrontBytesPerUs = 5e3;     // one front workgroup, next to the multiplying ones
+int lmhead_bf16_front_workgroups(int M, int B) {
+  if (M <= kSingleBlockRows) return 0;
+  return std::min(64, std::max(8, ceil_div(ceil_div(B, 4), 8) * 8));
+}
+constexpr int kWideWaves = 8;      // wavefronts per workgroup of every wide kernel: each one of a front workgroup is a worker
 
 template <int MT, int PF, int WPG, int KC, int NW, bool W_ONCE = false>
 hipError_t launch_wide(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
-                       int64_t ldz, const uint16_t* zeros, const FusedStats& fs, const StepArgs* draft_side,
+                       int64_t ldz, const uint16_t* zeros, const FusedStats& fs, const StepArgs* draft_side, int n_cu,
                        hipStream_t stream) {
   const int nks = Kp / 32, n_wtiles = Vp / kGemmColsPerWave;
   const int m_blocks = ceil_div(M, MT * 16);
@@ -665,8 +732,9 @@ hipError_t launch_wide(const uint16_t* H, int M, int d, const uint16_t* Wp, int 
   if (draft_side && fs.part) {
     ds = *draft_side;
     const PiecePlan& plan = ds.plan;
-    n_front = lmhead_bf16_front_workgroups(M, ds.B, ds.K);
-    const int workers = n_front > 0 ? n_front : col_tiles * m_blocks;
+    static_assert(WPG == kWideWaves, "the plan of the front workgroups counts on this many wavefronts each");
+    n_front = lmhead_bf16_front_workgroups(M, ds.B);
+    const int workers = n_front > 0 ? n_front * WPG : col_tiles * m_blocks;
     if (ds.K < 1 || plan.workers < 1 || plan.workers > workers || plan.base < 1 ||
         plan.base + (plan.more > 0) > kDraftPieces || plan.more < 0 || plan.more > ds.K ||
         (plan.workers < ds.K && (plan.base != 1 || plan.more != 0)))
@@ -723,20 +791,23 @@ int lmhead_bf16_fused_partials(int M, int Vp, int n_cu) {
 int lmhead_bf16_draft_workers(int M, int Vp, int B, int K, int n_cu) {
   const int nfine = lmhead_bf16_fused_partials(M, Vp, n_cu);
   if (nfine == 0) return 0;
-  return M > kSingleBlockRows ? lmhead_bf16_front_workgroups(M, B, K) : nfine;
+  return M > kSingleBlockRows ? lmhead_bf16_front_workgroups(M, B) * kWideWaves : nfine;
 }
 
 // Whether the LM-head launch should host the draft side (the draft rows' statistics, the drafted ids' lookups, and the
 // target rows' softmax partials from its epilogue).  With a single M-block the launch is bound by the weight stream
 // and a multiplying workgroup's piece of a draft row costs it about the 3 us that it would otherwise wait for its first
 // loads: hosted when a workgroup gets at most two rows.  With several M-blocks front workgroups take the draft side:
-// hosted when they finish within half the launch (about 6 us a row, 60 us per four sequences).
-bool lmhead_bf16_hosts_draft_side(int M, int d, int Vp, int B, int K, int n_cu) {
+// hosted when they are done within three quarters of the launch (their bytes at the rate above, 15 us per round of
+// lookups).
+bool lmhead_bf16_hosts_draft_side(int M, int d, int Vp, int B, int K, int V_d, int n_cu) {
   if (B < 1 || B > kFusedMaxB || K < 1) return false;
   const int workers = lmhead_bf16_draft_workers(M, Vp, B, K, n_cu);
   if (workers == 0) return false;
   if (M <= kSingleBlockRows) return K <= 2 * workers;
-  return ceil_div(K, workers) * 6.0 + ceil_div(B, 4 * workers) * 60.0 <= 0.5 * lmhead_launch_us(M, d, Vp);
+  const int n_front = workers / kWideWaves;
+  const double front_us = 2.0 * K * (double)V_d / (n_front * kFrontBytesPerUs) + ceil_div(B, 4 * n_front) * 15.0;
+  return front_us <= 0.75 * lmhead_launch_us(M, d, Vp);
 }
 
 hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* Wp, int Kp, int Vp, float* Z, int V_t,
@@ -759,32 +830,24 @@ hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* W
   if (tiles <= 9 && lmhead_bf16_tile_cols(M, Vp, n_cu) == 512) {
     // wavefronts of 64 columns, hidden slices of 64 columns and a ring two (twice as long) steps deep: the same bytes
     // in flight per CU as the 256-column shape
-    if (tiles <= 4) return launch_wide<4, 2, 8, 64, 4, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
-    if (tiles <= 6) return launch_wide<6, 2, 8, 64, 4, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
-    return launch_wide<9, 2, 8, 64, 4, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
+    if (tiles <= 4) return launch_wide<4, 2, 8, 64, 4, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
+    if (tiles <= 6) return launch_wide<6, 2, 8, 64, 4, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
+    return launch_wide<9, 2, 8, 64, 4, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
   }
-  if (tiles <= 2) return launch_wide<2, 4, 8, 128, 2, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
-  if (tiles <= 4) return launch_wide<4, 4, 8, 128, 2, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
-  if (tiles <= 6) return launch_wide<6, 4, 8, 128, 2, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
-  if (tiles <= 9) return launch_wide<9, 4, 8, 128, 2, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
-  // More than 144 rows run as several M-blocks per column tile; their weight streams meet in one L2.  This regime is
-  // bound by the L2 -> LDS traffic and by LDS reads, and the time of an M-block was measured to grow almost in
-  // proportion to its height (about 1.3 row tiles of fixed cost per block: 144, 256, 288 rows take 150, 251, 284 us at
-  // d = 4096, V_t = 128256), so the height that minimises blocks x (1.3 + row tiles) is taken: mostly the one that pads
-  // least.  Heights above 144 rows use hidden slices of 64 columns and a weight ring two steps deep to fit in LDS.
-  int best_mt = 9;
-  int best_cost = ceil_div(M, 144) * (13 + 10 * 9);
-  for (int mt : {10, 12, 14, 16, 18}) {
-    const int cost = ceil_div(M, 16 * mt) * (13 + 10 * mt);
-    if (cost <= best_cost) { best_cost = cost; best_mt = mt; }
-  }
+  if (tiles <= 2) return launch_wide<2, 4, 8, 128, 2, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
+  if (tiles <= 4) return launch_wide<4, 4, 8, 128, 2, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
+  if (tiles <= 6) return launch_wide<6, 4, 8, 128, 2, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
+  if (tiles <= 9) return launch_wide<9, 4, 8, 128, 2, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
+  // More than 144 rows run as several M-blocks per column tile (tall_block_tiles).  Heights above 144 rows use hidden
+  // slices of 64 columns and a weight ring two steps deep to fit in LDS.
+  const int best_mt = tall_block_tiles(M);
   switch (best_mt) {
-    case 10: return launch_wide<10, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
-    case 12: return launch_wide<12, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
-    case 14: return launch_wide<14, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
-    case 16: return launch_wide<16, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
-    case 18: return launch_wide<18, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
-    default: return launch_wide<9, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, stream);
+    case 10: return launch_wide<10, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
+    case 12: return launch_wide<12, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
+    case 14: return launch_wide<14, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
+    case 16: return launch_wide<16, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
+    case 18: return launch_wide<18, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
+    default: return launch_wide<9, 4, 8, 128, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
   }
 }
 

@@ -177,7 +177,7 @@ hipError_t launch_pack_w_bf16(const uint16_t* W, int d, int V_t, uint16_t* Wp, i
 int lmhead_bf16_fused_partials(int M, int Vp, int n_cu);
 // Whether a step of this shape lets the LM-head launch host the draft side and emit the partials (else the step runs
 // the statistics and the translation as launches of their own).
-bool lmhead_bf16_hosts_draft_side(int M, int d, int Vp, int B, int K, int n_cu);
+bool lmhead_bf16_hosts_draft_side(int M, int d, int Vp, int B, int K, int V_d, int n_cu);
 // workgroups of launch_lmhead_bf16 that share the draft rows (0: that shape leaves no partials and hosts nothing)
 int lmhead_bf16_draft_workers(int M, int Vp, int B, int K, int n_cu);
 // `fused` may be nullptr or have part == nullptr (no statistics); otherwise fused->nfine must be
