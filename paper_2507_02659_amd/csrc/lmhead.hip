@@ -697,14 +697,26 @@ double lmhead_launch_us(int M, int d, int Vp) { return std::max(2.0 * d * (doubl
 // grow almost in proportion to its height (about 1.3 row tiles of fixed cost per block: 144, 256, 288 rows take 150,
 // 251, 284 us at d = 4096, V_t = 128256), so the height that minimises blocks x (1.3 + row tiles) is taken: mostly the
 // one that pads least.
-int tall_block_tiles(int M) {
+int tall_block_tiles(int M, int* cost_out = nullptr) {
   int best_mt = 9;
   int best_cost = ceil_div(M, 144) * (13 + 10 * 9);
   for (int mt : {10, 12, 14, 16, 18}) {
     const int cost = ceil_div(M, 16 * mt) * (13 + 10 * mt);
     if (cost <= best_cost) { best_cost = cost; best_mt = mt; }
   }
+  if (cost_out) *cost_out = best_cost;
   return best_mt;
+}
+
+// Whether more than 144 rows run as 144-row M-blocks of the kernel whose wavefronts own 64 columns (512 per workgroup)
+// instead: a hidden fragment read from LDS then feeds four MFMAs instead of two, and the same cost comes out about
+// 7 % lower (measured: 425 rows 507 against 538 us per step, 432 rows 493 against 517, 576 rows 663 against 677,
+// 288 rows 358 against 361), but its accumulators leave room for 9 row tiles only, so it pays where M pads well to a
+// multiple of 144.
+bool tall_blocks_use_wide_wavefronts(int M) {
+  int cost = 0;
+  tall_block_tiles(M, &cost);
+  return 93 * ceil_div(M, 144) * (13 + 10 * 9) < 100 * cost;
 }
 
 // Front workgroups of a launch that hosts the draft side with several M-blocks: one per four sequences (the lookups go
@@ -775,7 +787,8 @@ hipError_t launch_pack_w_bf16(const uint16_t* W, int d, int V_t, uint16_t* Wp, i
 // take part.  512 columns per workgroup halve the rounds where that lets the launch fit into fewer, e.g. one round of
 // 251 workgroups instead of two of 256-column ones on 256 CUs for a 128256-column head (measured: 175 against 196 us).
 int lmhead_bf16_tile_cols(int M, int Vp, int n_cu) {
-  if (M <= 16 || M > kSingleBlockRows || n_cu < 1) return 256;
+  if (M > kSingleBlockRows) return tall_blocks_use_wide_wavefronts(M) ? 512 : 256;
+  if (M <= 16 || n_cu < 1) return 256;
   const int tiles256 = Vp / 256, tiles512 = ceil_div(Vp, 512);
   constexpr int kOutsideLoop = 40;                    // per round, in units of columns streamed
   const int cost256 = ceil_div(tiles256, n_cu) * (256 + kOutsideLoop);
@@ -843,6 +856,8 @@ hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* W
   if (tiles <= 9) return launch_wide<9, 4, 8, 128, 2, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
   // More than 144 rows run as several M-blocks per column tile (tall_block_tiles).  Heights above 144 rows use hidden
   // slices of 64 columns and a weight ring two steps deep to fit in LDS.
+  if (tall_blocks_use_wide_wavefronts(M))
+    return launch_wide<9, 2, 8, 64, 4>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
   const int best_mt = tall_block_tiles(M);
   switch (best_mt) {
     case 10: return launch_wide<10, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
