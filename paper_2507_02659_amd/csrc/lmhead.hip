@@ -692,31 +692,28 @@ constexpr int kSingleBlockRows = 144;
 // Rough duration of an LM-head launch: the weights stream at 6 TB/s or the product runs at 1 PFLOP/s, whichever is longer.
 double lmhead_launch_us(int M, int d, int Vp) { return std::max(2.0 * d * (double)Vp / 6.0e6, 2.0 * M * d * (double)Vp / 1.0e9); }
 
-// Row tiles per M-block when more than 144 rows run as several M-blocks per column tile (their weight streams meet in
-// one L2).  That regime is bound by the L2 -> LDS traffic and by LDS reads, and the time of an M-block was measured to
-// grow almost in proportion to its height (about 1.3 row tiles of fixed cost per block: 144, 256, 288 rows take 150,
-// 251, 284 us at d = 4096, V_t = 128256), so the height that minimises blocks x (1.3 + row tiles) is taken: mostly the
-// one that pads least.
-int tall_block_tiles(int M, int* cost_out = nullptr) {
-  int best_mt = 9;
-  int best_cost = ceil_div(M, 144) * (13 + 10 * 9);
+// How more than 144 rows run: as several M-blocks per column tile (their weight streams meet in one L2), of `tiles` row
+// tiles each, by the kernel whose wavefronts own 32 columns or by the one whose wavefronts own 64 (`wide`).  That regime
+// is bound by the L2 -> LDS traffic and by LDS reads, and the time of an M-block was measured to grow almost in
+// proportion to its height (about 1.3 row tiles of fixed cost per block: 144, 256, 288 rows take 150, 251, 284 us at
+// d = 4096, V_t = 128256), so the plan that minimises blocks x (1.3 + row tiles) is taken: mostly the height that pads
+// least.  With 64 columns per wavefront a hidden fragment read from LDS feeds four MFMAs instead of two and the same
+// cost comes out about 7 % lower, but the accumulators leave room for 11 row tiles at most.  Measured, us per step,
+// best 32-column plan against the 64-column one: 176 rows 264 / 244, 320 rows 417 / 386, 352 rows 461 / 408,
+// 425 rows 538 / 507, 432 rows 517 / 493, 576 rows 677 / 663, 1024 rows 1118 / 1076; 384 rows 468 / 519 (stays).
+struct TallPlan { int tiles; bool wide; };
+TallPlan tall_plan(int M) {
+  TallPlan best{9, false};
+  int best_cost = 100 * ceil_div(M, 144) * (13 + 10 * 9);
   for (int mt : {10, 12, 14, 16, 18}) {
-    const int cost = ceil_div(M, 16 * mt) * (13 + 10 * mt);
-    if (cost <= best_cost) { best_cost = cost; best_mt = mt; }
+    const int cost = 100 * ceil_div(M, 16 * mt) * (13 + 10 * mt);
+    if (cost <= best_cost) { best_cost = cost; best = TallPlan{mt, false}; }
   }
-  if (cost_out) *cost_out = best_cost;
-  return best_mt;
-}
-
-// Whether more than 144 rows run as 144-row M-blocks of the kernel whose wavefronts own 64 columns (512 per workgroup)
-// instead: a hidden fragment read from LDS then feeds four MFMAs instead of two, and the same cost comes out about
-// 7 % lower (measured: 425 rows 507 against 538 us per step, 432 rows 493 against 517, 576 rows 663 against 677,
-// 288 rows 358 against 361), but its accumulators leave room for 9 row tiles only, so it pays where M pads well to a
-// multiple of 144.
-bool tall_blocks_use_wide_wavefronts(int M) {
-  int cost = 0;
-  tall_block_tiles(M, &cost);
-  return 93 * ceil_div(M, 144) * (13 + 10 * 9) < 100 * cost;
+  for (int mt : {9, 10, 11}) {
+    const int cost = 93 * ceil_div(M, 16 * mt) * (13 + 10 * mt);
+    if (cost < best_cost) { best_cost = cost; best = TallPlan{mt, true}; }
+  }
+  return best;
 }
 
 // Front workgroups of a launch that hosts the draft side with several M-blocks: one per four sequences (the lookups go
@@ -787,7 +784,7 @@ hipError_t launch_pack_w_bf16(const uint16_t* W, int d, int V_t, uint16_t* Wp, i
 // take part.  512 columns per workgroup halve the rounds where that lets the launch fit into fewer, e.g. one round of
 // 251 workgroups instead of two of 256-column ones on 256 CUs for a 128256-column head (measured: 175 against 196 us).
 int lmhead_bf16_tile_cols(int M, int Vp, int n_cu) {
-  if (M > kSingleBlockRows) return tall_blocks_use_wide_wavefronts(M) ? 512 : 256;
+  if (M > kSingleBlockRows) return tall_plan(M).wide ? 512 : 256;
   if (M <= 16 || n_cu < 1) return 256;
   const int tiles256 = Vp / 256, tiles512 = ceil_div(Vp, 512);
   constexpr int kOutsideLoop = 40;                    // per round, in units of columns streamed
@@ -854,11 +851,17 @@ hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* W
   if (tiles <= 4) return launch_wide<4, 4, 8, 128, 2, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
   if (tiles <= 6) return launch_wide<6, 4, 8, 128, 2, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
   if (tiles <= 9) return launch_wide<9, 4, 8, 128, 2, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
-  // More than 144 rows run as several M-blocks per column tile (tall_block_tiles).  Heights above 144 rows use hidden
+  // More than 144 rows run as several M-blocks per column tile (tall_plan).  Heights above 144 rows use hidden
   // slices of 64 columns and a weight ring two steps deep to fit in LDS.
-  if (tall_blocks_use_wide_wavefronts(M))
-    return launch_wide<9, 2, 8, 64, 4>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
-  const int best_mt = tall_block_tiles(M);
+  const TallPlan plan = tall_plan(M);
+  if (plan.wide) {
+    switch (plan.tiles) {
+      case 10: return launch_wide<10, 2, 8, 64, 4>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
+      case 11: return launch_wide<11, 2, 8, 64, 4>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
+      default: return launch_wide<9, 2, 8, 64, 4>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
+    }
+  }
+  const int best_mt = plan.tiles;
   switch (best_mt) {
     case 10: return launch_wide<10, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
     case 12: return launch_wide<12, 2, 8, 64, 2>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
