@@ -68,7 +68,7 @@ typedef struct ot_ngram_cache ot_ngram_cache; /* owns the device hash table of o
 /* ---- ot_verify_init ----------------------------------------------------------------------------------- */
 /* The draft rows' softmax statistics and what the drafted ids look up for the translation (Eq. 1: the drafted logit,
  * the direct image, the n-gram cache probes) need nothing from the LM head.  Where the bf16 LM-head kernel supports it
- * (more than 16 rows, at most 255 sequences) the LM-head launch itself can do that work: with up to 144 rows, where the
+ * (more than 16 rows, at most 255 sequences) the LM-head launch itself can do that work: with up to 176 rows, where the
  * launch is bound by the weight stream, every multiplying workgroup takes a piece of a draft row while its first loads
  * are in flight; with more rows a few workgroups at the front of the launch take all of it.  The launch then also
  * leaves the target rows' softmax partials, and one launch follows it (window walk, acceptance test, final draw)
@@ -80,7 +80,7 @@ typedef struct ot_ngram_cache ot_ngram_cache; /* owns the device hash table of o
  *   - more than 255 sequences in a step: the same, and the translation with the acceptance test gets a launch of its
  *     own as well (two launches more, about 25 us at 256 sequences with a 32000-id draft vocabulary);
  *   - OT_DRAFT_SIDE_AUTO also chooses the first of these when hosting would lengthen the LM-head launch: more than two
- *     draft rows per multiplying workgroup (up to 144 rows), or front workgroups that would need more than half
+ *     draft rows per multiplying workgroup (up to 176 rows), or front workgroups that would need more than half
  *     of the launch (above).                                                                                     */
 #define OT_DRAFT_SIDE_AUTO        0   /* decide per step from its shape (estimate of both durations)               */
 #define OT_DRAFT_SIDE_IN_LM_HEAD  1   /* inside the LM-head launch whenever the kernel supports the shape          */

@@ -8,7 +8,7 @@
 //     fragments of 64 adjacent columns per 32-deep step are adjacent.  A wavefront streams the fragments of its
 //     columns with fully coalesced 1 KB loads: no transpose anywhere.
 //   * Every weight is used by exactly one wavefront, which keeps accumulators for ALL rows of the M-block
-//     (up to 9 x 16 rows while the product is bound by HBM), so W is read from HBM once.  More than 144 rows run as
+//     (up to 11 x 16 rows while the product is bound by HBM), so W is read from HBM once.  More than 176 rows run as
 //     several M-blocks of up to 18 x 16 rows per column tile, scheduled so that they share W in one L2.
 //   * From 17 rows on, both operands travel by direct global->LDS loads.  The hidden rows, shared by the wavefronts
 //     of a workgroup, go through double-buffered slices 128 (or, for the tall M-blocks, 64) columns deep (swizzled
@@ -686,13 +686,15 @@ __global__ __launch_bounds__(256) void lmhead_f32_kernel(const float* __restrict
     if (i < rows) Z[(int64_t)(m0 + i) * ldz + n] = acc[i];
 }
 
-// Rows above which an M-block is split (16 rows per tile, at most 9 tiles in a block of the single-block shapes).
-constexpr int kSingleBlockRows = 144;
+// Rows above which an M-block is split: up to 11 row tiles run as one block that streams every weight once (9 with
+// either wavefront width, 10 and 11 only with 64 columns per wavefront, whose accumulators just fit).  Measured at 160 /
+// 176 rows: 217 / 225 us per step as one block against 244 / 246 us as two.
+constexpr int kSingleBlockRows = 176;
 
 // Rough duration of an LM-head launch: the weights stream at 6 TB/s or the product runs at 1 PFLOP/s, whichever is longer.
 double lmhead_launch_us(int M, int d, int Vp) { return std::max(2.0 * d * (double)Vp / 6.0e6, 2.0 * M * d * (double)Vp / 1.0e9); }
 
-// How more than 144 rows run: as several M-blocks per column tile (their weight streams meet in one L2), of `tiles` row
+// How more than 176 rows run: as several M-blocks per column tile (their weight streams meet in one L2), of `tiles` row
 // tiles each, by the kernel whose wavefronts own 32 columns or by the one whose wavefronts own 64 (`wide`).  That regime
 // is bound by the L2 -> LDS traffic and by LDS reads, and the time of an M-block was measured to grow almost in
 // proportion to its height (about 1.3 row tiles of fixed cost per block: 144, 256, 288 rows take 150, 251, 284 us at
@@ -785,6 +787,7 @@ hipError_t launch_pack_w_bf16(const uint16_t* W, int d, int V_t, uint16_t* Wp, i
 // 251 workgroups instead of two of 256-column ones on 256 CUs for a 128256-column head (measured: 175 against 196 us).
 int lmhead_bf16_tile_cols(int M, int Vp, int n_cu) {
   if (M > kSingleBlockRows) return tall_plan(M).wide ? 512 : 256;
+  if (M > 144) return 512;             // 10 or 11 row tiles in one block: only the 64-column wavefronts hold them
   if (M <= 16 || n_cu < 1) return 256;
   const int tiles256 = Vp / 256, tiles512 = ceil_div(Vp, 512);
   constexpr int kOutsideLoop = 40;                    // per round, in units of columns streamed
@@ -840,6 +843,8 @@ hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* W
                        reinterpret_cast<const uint4*>(Wp), nks, Z, V_t, ldz);
     return hipGetLastError();
   }
+  if (tiles == 10) return launch_wide<10, 2, 8, 64, 4, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
+  if (tiles == 11) return launch_wide<11, 2, 8, 64, 4, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
   if (tiles <= 9 && lmhead_bf16_tile_cols(M, Vp, n_cu) == 512) {
     // wavefronts of 64 columns, hidden slices of 64 columns and a ring two (twice as long) steps deep: the same bytes
     // in flight per CU as the 256-column shape
@@ -851,7 +856,7 @@ hipError_t launch_lmhead_bf16(const uint16_t* H, int M, int d, const uint16_t* W
   if (tiles <= 4) return launch_wide<4, 4, 8, 128, 2, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
   if (tiles <= 6) return launch_wide<6, 4, 8, 128, 2, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
   if (tiles <= 9) return launch_wide<9, 4, 8, 128, 2, true>(H, M, d, Wp, Kp, Vp, Z, V_t, ldz, zeros, fs, draft_side, n_cu, stream);
-  // More than 144 rows run as several M-blocks per column tile (tall_plan).  Heights above 144 rows use hidden
+  // More than 176 rows run as several M-blocks per column tile (tall_plan).  Heights above 144 rows use hidden
   // slices of 64 columns and a weight ring two steps deep to fit in LDS.
   const TallPlan plan = tall_plan(M);
   if (plan.wide) {

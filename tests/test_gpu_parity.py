@@ -306,8 +306,8 @@ def test_more_sequences_than_the_lm_head_stages():
     _run_and_compare(make_case(spec))
 
 
-@pytest.mark.parametrize("M,B", [(16, 2), (17, 2), (33, 3), (96, 6), (97, 6), (144, 9), (145, 9), (288, 12), (289, 12), (300, 255),
-                                 (300, 256), (433, 20)])
+@pytest.mark.parametrize("M,B", [(16, 2), (17, 2), (33, 3), (96, 6), (97, 6), (144, 9), (145, 9), (160, 10), (176, 11), (177, 11), (288, 12), (289, 12),
+                                 (300, 255), (300, 256), (320, 20), (352, 16), (433, 20)])
 def test_row_count_boundaries_end_to_end(M, B):
     """Whole steps from hidden states at the row counts where the LM head changes kernel, M-block size or the number of
     M-blocks, and at the sequence count where its epilogue stops emitting the row statistics."""
